@@ -1,0 +1,163 @@
+/*
+ * C ABI of the MI355X (gfx950) MoE megakernel hot path.
+ *
+ * One GPU's share of a tile-granular Mixture-of-Experts layer (paper section
+ * 2.1: gate -> dispatch -> expert compute -> combine; section 2.3: one
+ * persistent kernel working on tiles; section 2.3 "put-with-signal" and
+ * section 4.1 / Algorithm 1: how finished tiles are announced).
+ *
+ * Conventions
+ *   - Every call returns a moe_status_t (0 = MOE_OK, negative = error).  The
+ *     library never throws, aborts or prints.
+ *   - Every pointer is a DEVICE pointer owned by the caller unless marked
+ *     "host".  The library allocates nothing; scratch comes from a caller
+ *     workspace of moe_workspace_bytes() bytes, 256-byte aligned, prepared once
+ *     by moe_workspace_init().
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without waiting for it.
+ *   - Tensors are contiguous and row-major.  Element type of x, Wg, W1, W3,
+ *     W2, staging and out is `dtype` (fp32, or bf16 as raw 16-bit patterns).
+ *     Indices are int32, gate weights fp32.
+ *   - Host-detectable misuse (NULL required pointer, k > E, R not dividing T,
+ *     unsupported sizes) is reported before anything is launched.
+ *
+ * Notation: T tokens, d model dim, E local experts, k experts per token,
+ * f FFN dim, R destinations.  Slot s = t*k + j is token t's j-th choice;
+ * N = T*k slots.  Token t belongs to destination r = t / (T/R); destination
+ * r's partition of `staging` is rows [r*(T/R)*k, (r+1)*(T/R)*k).
+ */
+#ifndef MOE_H
+#define MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_INVALID_ARG = -1, /* NULL pointer, k > E, R does not divide T, ... */
+    MOE_ERR_UNSUPPORTED = -2, /* legal problem this build has no kernel for    */
+    MOE_ERR_WORKSPACE = -3,   /* workspace NULL or misaligned                  */
+    MOE_ERR_NOT_READY = -4,   /* (device status) a flag was not at `epoch`     */
+    MOE_ERR_HIP = -5,         /* a HIP runtime call failed                     */
+    MOE_ERR_TIMEOUT = -6,     /* (device status) a bounded wait expired        */
+    MOE_ERR_BAD_ROUTING = -7  /* (device status) expert id outside [0, E)      */
+} moe_status_t;
+
+typedef enum { MOE_DT_F32 = 0, MOE_DT_BF16 = 1 } moe_dtype_t;
+
+/* How a finished output tile is announced (section 2.3, section 4.1):
+ *   PER_TILE  coupled put-with-signal: every published tile is written, then a
+ *             release fence, then its flag (PUT -> FENCE -> SIGNAL per tile).
+ *   PER_DEST  decoupled signaling (Algorithm 1) with one group per
+ *             destination: tiles are written back to back and counted in a
+ *             per-destination counter; whoever completes the count issues ONE
+ *             fence and then stores all flags of that destination. */
+typedef enum { MOE_SIGNAL_PER_TILE = 0, MOE_SIGNAL_PER_DEST = 1 } moe_signal_mode_t;
+
+/* Memory scope of the fence that precedes flag stores and of the flag
+ * accesses themselves: this GPU only, or GPU + host + peers. */
+typedef enum { MOE_SCOPE_AGENT = 0, MOE_SCOPE_SYSTEM = 1 } moe_fence_scope_t;
+
+typedef struct {
+    int32_t T, d, E, k, f, R; /* R must divide T                                   */
+    int32_t dtype;            /* moe_dtype_t                                        */
+    int32_t tile_m, tile_n;   /* publish tile rows x cols; 0 = 128 x 64 (the tile   */
+                              /* of section 2.3).  tile_m in {32,64,128}, tile_n in */
+                              /* {64,128}                                           */
+    int32_t signal_mode;      /* moe_signal_mode_t                                  */
+    int32_t fence_scope;      /* moe_fence_scope_t                                  */
+    uint32_t epoch;           /* value a flag takes when its tile is ready; nonzero */
+                              /* and different from the previous call's             */
+} moe_problem_t;
+
+/* number of 64-bit counters moe_megakernel_forward writes to `stats` */
+#define MOE_NUM_STATS 8
+/* stats[0] release fences issued right before flag stores (per tile, or per destination)
+ * stats[1] flags stored                 stats[2] publish tiles written
+ * stats[3] per-compute-tile releases that only feed a destination counter (PER_DEST)
+ * stats[4] GEMM1 compute tiles          stats[5] GEMM2 compute tiles
+ * stats[6] bounded waits that expired   stats[7] device status (a moe_status_t, 0 = ok) */
+
+/* Host, pure: bytes of workspace a problem needs / upper bound on the number
+ * of flags (uint32 each) the caller must provide; 0 if the problem is invalid. */
+size_t moe_workspace_bytes(const moe_problem_t *p);
+size_t moe_num_flags(const moe_problem_t *p);
+
+/* Host, pure: static string for a status code. */
+const char *moe_status_string(int status);
+
+/* Zero the control part of a fresh workspace.  Call once after allocating it
+ * (and again after a call reported MOE_ERR_TIMEOUT); every other entry point
+ * leaves the workspace ready for the next call. */
+int moe_workspace_init(const moe_problem_t *p, void *workspace, void *stream);
+
+/*
+ * Gate (section 2.1 step 1).  logits[t,e] = sum_i x[t,i] Wg[i,e] + gate_bias[e]
+ * accumulated in fp64; topk_idx[t,:] = the k largest in descending order
+ * (equal scores: lower expert id first); topk_w[t,j] = softmax over the k
+ * chosen logits (sums to 1).
+ *   x [T,d], Wg [d,E] in, dtype; gate_bias [E] fp32 in, may be NULL.
+ *   topk_idx [T,k] int32 out; topk_w [T,k] fp32 out.   E <= 256.
+ */
+int moe_route(const moe_problem_t *p, const void *x, const void *Wg, const float *gate_bias,
+              int32_t *topk_idx, float *topk_w, void *stream);
+
+/*
+ * Dispatch in its local form (section 2.1 step 2; section 2.3 "group tokens
+ * into tiles"): stable counting sort of the N slots by expert.
+ *   topk_idx [T,k] in (every id in [0,E), the k ids of a token distinct).
+ *   counts [E], offsets [E+1] out: histogram and its exclusive scan.
+ *   perm [N] out: slot at sorted position p (slots of one expert ascending);
+ *   inv_perm [N] out: inverse.  x_perm [N,d] out, may be NULL:
+ *   x_perm[p,:] = x[perm[p]/k,:].  workspace as above.
+ */
+int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx, int32_t *counts,
+                 int32_t *offsets, int32_t *perm, int32_t *inv_perm, void *x_perm,
+                 void *workspace, void *stream);
+
+/*
+ * The whole layer in ONE persistent kernel (sections 2.1, 2.3, 4.1): gate,
+ * dispatch, per-expert SwiGLU FFN  y = (silu(x W1[e]) * (x W3[e])) W2[e]
+ * as a grouped GEMM, publication of every finished y tile into `staging`
+ * (row s of staging = expert output for slot s) with a ready flag, and the
+ * weighted combine out[t] = sum_j topk_w[t,j] * staging[t*k+j], which waits on
+ * the flags.
+ *   Wg == NULL: routing is precomputed; topk_idx / topk_w are inputs.
+ *   W1, W3 [E,d,f], W2 [E,f,d] in.
+ *   topk_idx, topk_w, counts, offsets, perm, inv_perm: as above (outputs).
+ *   slot_flag [N] int32 out: index of the first flag (column block 0) of the
+ *     publish tile that carries slot s; column block c is slot_flag[s] + c.
+ *   staging [N,d] out; flags [moe_num_flags()] uint32 in/out: entries of
+ *     tiles published by this call are set to p->epoch; out [T,d] out.
+ *   stats [MOE_NUM_STATS] uint64 out, may be NULL.
+ * Flags are numbered destination-major, then expert, then row block of tile_m
+ * rows counted from the expert's first row, then column block of tile_n.
+ */
+int moe_megakernel_forward(const moe_problem_t *p, const void *x, const void *Wg,
+                           const float *gate_bias, const void *W1, const void *W3, const void *W2,
+                           int32_t *topk_idx, float *topk_w, int32_t *counts, int32_t *offsets,
+                           int32_t *perm, int32_t *inv_perm, int32_t *slot_flag, void *staging,
+                           uint32_t *flags, void *out, uint64_t *stats, void *workspace,
+                           void *stream);
+
+/*
+ * Combine alone (section 2.1 step 4): out[t] = sum_j topk_w[t,j] *
+ * staging[t*k+j] in fp32, rounded once to dtype.  Before reading slot s the
+ * kernel checks, with acquire loads at p->fence_scope, that every flag
+ * slot_flag[s] + c (c < ceil(d/tile_n)) equals p->epoch; if one does not,
+ * *status_dev is set to MOE_ERR_NOT_READY (the row is still combined from
+ * whatever staging holds).  slot_flag == NULL skips the check.
+ *   status_dev: int32 on the device, written only on failure; may be NULL.
+ */
+int moe_combine(const moe_problem_t *p, const void *staging, const uint32_t *flags,
+                const int32_t *slot_flag, const float *topk_w, void *out, int32_t *status_dev,
+                void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H */

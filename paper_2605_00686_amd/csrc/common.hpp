@@ -1,0 +1,173 @@
+// Shared device-side definitions: kernel argument block, workspace layout,
+// bounded waits and scoped fences.  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/moe.h"
+
+namespace moe {
+
+typedef unsigned long long u64;
+typedef uint32_t u32;
+typedef unsigned short bf16_t;  // raw bf16 bits
+
+constexpr int kThreads = 256;       // every kernel here runs 4 wavefronts per workgroup
+constexpr int kPermBlock = 64;      // tokens per permutation block (one bit each in a 64-bit mask)
+constexpr int kRouteTokens = 16;    // tokens per gate task
+constexpr int kMaxExperts = 256;    // gate / plan limits
+constexpr int kMaxDest = 1024;
+constexpr u64 kWaitTicks = 400000000ull;  // 4 s of the 100 MHz wall clock: bound of every in-kernel wait
+
+// Control block at the start of the workspace.  All zero between calls: the
+// last workgroup to leave a kernel clears what the kernel dirtied.
+struct Ctrl {
+    u32 next_task;   // persistent scheduler: next task to hand out
+    u32 route_done;  // gate tasks finished
+    u32 plan_done;   // 1 once offsets / tables are valid
+    u32 perm_done;   // permutation blocks finished
+    u32 exit_count;  // workgroups that left the kernel
+    u32 error;       // first device status (moe_status_t as positive number), 0 = ok
+    u32 n_rb;        // row blocks in use (all experts)
+    u32 n_flags;     // publish tiles / flags in use
+    u32 pad[8];
+    u64 stats[MOE_NUM_STATS];
+};
+
+// GEMM tiling chosen on the host.
+struct Tiling {
+    int BM;     // rows of a compute tile (multiple of tile_m)
+    int BN1;    // h columns per GEMM1 tile
+    int BN2;    // y columns per GEMM2 tile
+    int NT1;    // ceil(f / BN1)
+    int NT2;    // ceil(d / BN2)
+    int maxRB;  // upper bound on row blocks: N / BM + E
+};
+
+// Everything a kernel needs, passed by value.
+struct KArgs {
+    int T, d, E, k, f, R;
+    int dtype, tile_m, tile_n, signal_mode, fence_scope;
+    u32 epoch;
+    int N, per_dest, ncb;  // slots, tokens per destination, column blocks per row
+    int nPB, nRT, nCT;     // permutation blocks, gate tasks, combine tasks
+    int comb_tokens;       // tokens per combine task
+    Tiling tl;
+    // task ranges of the persistent scheduler: [route | plan | perm | g1 | g2 | combine)
+    int t_plan, t_perm, t_g1, t_g2, t_comb, t_end;
+    // caller tensors
+    const void *x, *Wg;
+    const float *bias;
+    const void *W1, *W3, *W2;
+    int32_t *idx;
+    float *w;
+    int32_t *counts, *offsets, *perm, *inv_perm, *slot_flag;
+    void *staging;
+    u32 *flags;
+    void *out;
+    u64 *stats;
+    void *x_perm;
+    int32_t *status_dev;
+    // workspace
+    Ctrl *ctrl;
+    int32_t *blk_hist;         // [nPB][E] slots of block b routed to e
+    int32_t *blk_base;         // [nPB][E] sorted position of block b's first slot of e
+    int32_t *seg_cnt;          // [E][R]
+    int32_t *seg_begin;        // [E][R] expert-local first row of (e, r)
+    int32_t *flag_base;        // [R][E]
+    int32_t *dest_flag_begin;  // [R+1]
+    u32 *dest_counter;         // [R] publish tiles written so far (PER_DEST)
+    int32_t *rb_base;          // [E+1] first row block of expert e
+    int32_t *rb_expert;        // [maxRB]
+    u32 *h_ready;              // [maxRB] GEMM1 tiles finished per row block
+    void *h;                   // [N][f]
+    size_t zero_bytes;         // bytes from ctrl that must be zero between calls
+};
+
+__device__ __forceinline__ u64 now_ticks() { return wall_clock64(); }
+
+__device__ __forceinline__ void set_error(Ctrl *c, int status) {
+    atomicCAS(&c->error, 0u, (u32)(-status));
+}
+
+__device__ __forceinline__ u32 ld_relaxed_agent(const u32 *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ u32 ld_relaxed(const u32 *p, int system_scope) {
+    return system_scope ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM)
+                        : __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_relaxed(u32 *p, u32 v, int system_scope) {
+    if (system_scope)
+        __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    else
+        __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void fence_release(int system_scope) {
+    if (system_scope)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "");
+    else
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+}
+__device__ __forceinline__ void fence_acquire(int system_scope) {
+    if (system_scope)
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");
+    else
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+}
+
+// Workgroup barrier that also waits for this wavefront's outstanding global
+// stores.  __syncthreads() alone only drains LDS traffic; a store still in
+// flight when ANOTHER wavefront of the workgroup issues the release fence would
+// miss that fence's cache write-back and stay invisible to other XCDs.
+__device__ __forceinline__ void sync_stores() {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+}
+
+// Spin until *p >= target (agent scope), bounded by the wall clock and by the
+// global error flag so that a broken dependency drains the grid instead of
+// hanging it.  Called by one thread; returns false on time-out.
+__device__ __forceinline__ bool wait_ge(Ctrl *c, const u32 *p, u32 target) {
+    if (ld_relaxed_agent(p) >= target) {
+        fence_acquire(0);
+        return true;
+    }
+    const u64 t0 = now_ticks();
+    int spins = 0;
+    while (true) {
+        if (ld_relaxed_agent(p) >= target) break;
+        __builtin_amdgcn_s_sleep(2);
+        if ((++spins & 63) == 0) {
+            if (ld_relaxed_agent(&c->error) != 0) return false;
+            if (now_ticks() - t0 > kWaitTicks) {
+                set_error(c, MOE_ERR_TIMEOUT);
+                atomicAdd(&c->stats[6], 1ull);
+                return false;
+            }
+        }
+    }
+    fence_acquire(0);
+    return true;
+}
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((u32)b) << 16); }
+// round to nearest even; inputs here are finite
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    u32 u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ u32 pack_bf16x2(float lo, float hi) {
+    return (u32)f32_to_bf16(lo) | ((u32)f32_to_bf16(hi) << 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float load(const float *p, size_t i) { return p[i]; }
+};
+template <> struct Elem<bf16_t> {
+    static __device__ __forceinline__ float load(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
+};
+
+}  // namespace moe

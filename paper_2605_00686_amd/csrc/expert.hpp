@@ -1,0 +1,360 @@
+// Grouped SwiGLU FFN tiles, publication of finished output tiles with ready
+// flags (paper sections 2.3 and 4.1), and the weighted combine (section 2.1
+// step 4).
+#pragma once
+#include "common.hpp"
+#include "gemm_bf16.hpp"
+#include "gemm_f32.hpp"
+
+namespace moe {
+
+// ---- GEMM policies: element type + tile shape + main loop
+template <class C>
+struct Bf16Policy {
+    using ET = bf16_t;
+    static constexpr int BM = C::BM, BN1 = C::BN / 2, BN2 = C::BN;
+    static constexpr int C_STRIDE = C::C_STRIDE;
+    static constexpr int SMEM_MAIN = C::SMEM_MAIN;
+    template <bool GATED, class RowPtr>
+    static __device__ __forceinline__ void gemm(RowPtr rp, const ET *B0, const ET *B1, int ldb, int ncols, int K,
+                                                char *smem) {
+        gemm_tile_bf16<C, GATED>(rp, B0, B1, ldb, ncols, K, smem);
+    }
+};
+struct F32Policy {
+    using ET = float;
+    static constexpr int BM = TileF32::BM, BN1 = TileF32::BN, BN2 = TileF32::BN;
+    static constexpr int C_STRIDE = TileF32::C_STRIDE;
+    static constexpr int SMEM_MAIN = TileF32::SMEM_MAIN;
+    template <bool GATED, class RowPtr>
+    static __device__ __forceinline__ void gemm(RowPtr rp, const ET *B0, const ET *B1, int ldb, int ncols, int K,
+                                                char *smem) {
+        gemm_tile_f32<GATED>(rp, B0, B1, ldb, ncols, K, smem);
+    }
+};
+// LDS after the GEMM region: per-row slot / destination, publish row-tile list
+template <class P>
+constexpr int tile_smem_bytes() {
+    return P::SMEM_MAIN + (3 * P::BM + 8) * 4;
+}
+
+using CfgL = TileCfg<4, 4, 2, 2>;  // 256 x 256, wavefront 128 x 128
+using CfgM = TileCfg<2, 4, 2, 2>;  // 128 x 256, wavefront  64 x 128
+using CfgS = TileCfg<1, 2, 1, 4>;  //  32 x 256, wavefront  32 x  64
+
+struct TileInfo {
+    int e, rb, row0, nrows, lrow0, n0, ncols;
+    bool valid;
+};
+
+// Task -> tile.  Tiles of one expert are consecutive; inside an expert the
+// column tile varies slowest, so tiles running at the same time share one
+// weight column block and the expert's rows (the re-read operand is the small
+// one and stays in cache).
+__device__ __forceinline__ TileInfo decode_tile(const KArgs &a, int lt, int NT, int BN, int total_cols) {
+    TileInfo ti;
+    ti.valid = false;
+    const int vrb = lt / NT;
+    if (vrb >= (int)a.ctrl->n_rb) return ti;
+    const int e = a.rb_expert[vrb];
+    const int base = a.rb_base[e];
+    const int nrb = a.rb_base[e + 1] - base;
+    const int loc = lt - base * NT;
+    const int ct = loc / nrb, rbl = loc % nrb;
+    ti.e = e;
+    ti.rb = base + rbl;
+    ti.lrow0 = rbl * a.tl.BM;
+    ti.row0 = a.offsets[e] + ti.lrow0;
+    ti.nrows = min(a.tl.BM, a.offsets[e + 1] - ti.row0);
+    ti.n0 = ct * BN;
+    ti.ncols = min(BN, total_cols - ti.n0);
+    ti.valid = true;
+    return ti;
+}
+
+// GEMM1 + SwiGLU: h[rows of the block, n0 .. n0+ncols) = silu(x W1[e]) * (x W3[e]).
+// Rows are gathered straight from x through perm: the permuted activations are
+// never materialised.
+template <class P>
+__device__ void g1_tile(const KArgs &a, int lt, char *smem) {
+    using ET = typename P::ET;
+    const TileInfo ti = decode_tile(a, lt, a.tl.NT1, P::BN1, a.f);
+    if (!ti.valid) return;
+    const ET *x = (const ET *)a.x;
+    const int N = a.N;
+    auto rowptr = [&](int r) {
+        int s = a.perm[ti.row0 + min(r, ti.nrows - 1)];
+        s = min(max(s, 0), N - 1);
+        return x + (size_t)(s / a.k) * a.d;
+    };
+    const size_t wofs = (size_t)ti.e * a.d * a.f + ti.n0;
+    P::template gemm<true>(rowptr, (const ET *)a.W1 + wofs, (const ET *)a.W3 + wofs, a.f, ti.ncols, a.d, smem);
+    const int ppr = ti.ncols * (int)sizeof(ET) / 16;
+    char *h = (char *)a.h;
+    for (int q = threadIdx.x; q < ti.nrows * ppr; q += kThreads) {
+        const int r = q / ppr, c = q % ppr;
+        *(uint4 *)(h + ((size_t)(ti.row0 + r) * a.f + ti.n0) * sizeof(ET) + c * 16) =
+            *(const uint4 *)(smem + r * P::C_STRIDE + c * 16);
+    }
+    sync_stores();
+    if (threadIdx.x == 0) {
+        fence_release(0);
+        atomicAdd(&a.h_ready[ti.rb], 1u);
+        atomicAdd(&a.ctrl->stats[4], 1ull);
+    }
+}
+
+// Publish the y tile sitting in the LDS C tile.  A publish tile is the part of
+// the compute tile that lies in one (row block of tile_m rows, destination,
+// column block of tile_n columns); each has its own ready flag.
+//   PER_TILE: for every publish tile in turn: write it, barrier, release fence, flag
+//             (the coupled PUT -> FENCE -> SIGNAL of section 2.3).
+//   PER_DEST: write the whole compute tile, one release so the rows may be counted,
+//             add the publish tiles to their destination's counter (Algorithm 1,
+//             phase 1).  Whoever completes a destination's count is its leader: one
+//             fence at the requested scope, then all flags of that destination, stored
+//             by a whole wavefront (phase 2; lane-parallel signals as in appendix B).
+template <class P>
+__device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
+    using ET = typename P::ET;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int *s_slot = (int *)(smem + P::SMEM_MAIN);  // [BM] slot (= staging row) of local row r
+    int *s_dest = s_slot + P::BM;                // [BM] destination of local row r
+    int *s_seg = s_dest + P::BM;                 // [BM+1] first local row of publish row-tile i
+    int *s_nseg = s_seg + P::BM + 1;
+    const int N = a.N;
+    for (int r = tid; r < ti.nrows; r += kThreads) {
+        int s = a.perm[ti.row0 + r];
+        s = min(max(s, 0), N - 1);
+        s_slot[r] = s;
+        s_dest[r] = (s / a.k) / a.per_dest;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        int cnt = 0;
+        for (int base = 0; base < ti.nrows; base += 64) {
+            const int r = base + lane;
+            const bool st = r < ti.nrows && (r == 0 || ((ti.lrow0 + r) % a.tile_m) == 0 || s_dest[r] != s_dest[r - 1]);
+            const u64 m = __ballot(st);
+            if (st) s_seg[cnt + __popcll(m & ((1ull << lane) - 1ull))] = r;
+            cnt += __popcll(m);
+        }
+        if (lane == 0) {
+            s_seg[cnt] = ti.nrows;
+            *s_nseg = cnt;
+        }
+    }
+    __syncthreads();
+    const int nseg = *s_nseg;
+    const int cbn = (ti.ncols + a.tile_n - 1) / a.tile_n;  // column blocks in this compute tile
+    const int cb0 = ti.n0 / a.tile_n;
+    const int ES = (int)sizeof(ET);
+    char *staging = (char *)a.staging;
+    const int sys = a.fence_scope;
+
+    auto copy_rows = [&](int r0, int r1, int p0, int p1) {  // 16-byte pieces [p0, p1) of rows [r0, r1)
+        const int w = p1 - p0;
+        for (int q = tid; q < (r1 - r0) * w; q += kThreads) {
+            const int r = r0 + q / w, c = p0 + q % w;
+            *(uint4 *)(staging + ((size_t)s_slot[r] * a.d + ti.n0) * ES + c * 16) =
+                *(const uint4 *)(smem + r * P::C_STRIDE + c * 16);
+        }
+    };
+
+    if (a.signal_mode == MOE_SIGNAL_PER_TILE) {
+        for (int i = 0; i < nseg; ++i) {
+            const int r0 = s_seg[i], r1 = s_seg[i + 1];
+            for (int j = 0; j < cbn; ++j) {
+                const int p0 = j * a.tile_n * ES / 16;
+                const int p1 = min((j + 1) * a.tile_n, ti.ncols) * ES / 16;
+                copy_rows(r0, r1, p0, p1);
+                sync_stores();
+                if (tid == 0) {
+                    fence_release(sys);
+                    st_relaxed(&a.flags[a.slot_flag[s_slot[r0]] + cb0 + j], a.epoch, sys);
+                }
+            }
+        }
+        if (tid == 0) {
+            const u64 n = (u64)nseg * cbn;
+            atomicAdd(&a.ctrl->stats[0], n);
+            atomicAdd(&a.ctrl->stats[1], n);
+            atomicAdd(&a.ctrl->stats[2], n);
+        }
+    } else {
+        copy_rows(0, ti.nrows, 0, ti.ncols * ES / 16);
+        sync_stores();
+        if (wave == 0) {
+            fence_release(0);  // the rows of this tile may now be counted
+            u64 n_fence = 0, n_flag = 0;
+            for (int base = 0; base < nseg; base += 64) {
+                const int i = base + lane;
+                bool lead = false;
+                int dst = 0;
+                if (i < nseg) {
+                    dst = s_dest[s_seg[i]];
+                    const u32 expect = (u32)(a.dest_flag_begin[dst + 1] - a.dest_flag_begin[dst]);
+                    const u32 old = atomicAdd(&a.dest_counter[dst], (u32)cbn);
+                    lead = (old + (u32)cbn == expect);
+                }
+                u64 m = __ballot(lead);
+                while (m) {
+                    const int src = __ffsll((long long)m) - 1;
+                    m &= m - 1;
+                    const int dd = __shfl(dst, src, 64);
+                    fence_acquire(0);    // every tile counted for dd is visible here
+                    fence_release(sys);  // the one fence of this destination
+                    const int f0 = a.dest_flag_begin[dd], f1 = a.dest_flag_begin[dd + 1];
+                    for (int fi = f0 + lane; fi < f1; fi += 64) st_relaxed(&a.flags[fi], a.epoch, sys);
+                    if (lane == 0) __hip_atomic_store(&a.dest_counter[dd], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    n_fence += 1;
+                    n_flag += (u64)(f1 - f0);
+                }
+            }
+            if (lane == 0) {
+                if (n_fence) {
+                    atomicAdd(&a.ctrl->stats[0], n_fence);
+                    atomicAdd(&a.ctrl->stats[1], n_flag);
+                }
+                atomicAdd(&a.ctrl->stats[2], (u64)nseg * cbn);
+                atomicAdd(&a.ctrl->stats[3], 1ull);
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// GEMM2 + publish: y[rows of the block, n0 .. n0+ncols) = h W2[e], written to
+// staging row perm[p] (the slot that asked for it).  The caller has already
+// waited for the block's h rows.
+template <class P>
+__device__ void g2_tile(const KArgs &a, const TileInfo &ti, char *smem) {
+    using ET = typename P::ET;
+    const ET *h = (const ET *)a.h;
+    auto rowptr = [&](int r) { return h + (size_t)(ti.row0 + min(r, ti.nrows - 1)) * a.f; };
+    const ET *B0 = (const ET *)a.W2 + (size_t)ti.e * a.f * a.d + ti.n0;
+    P::template gemm<false>(rowptr, B0, B0, a.d, ti.ncols, a.f, smem);
+    publish_tile<P>(a, ti, smem);
+    if (threadIdx.x == 0) atomicAdd(&a.ctrl->stats[5], 1ull);
+}
+
+// ---- combine
+template <typename ET>
+struct Vec16;
+template <>
+struct Vec16<bf16_t> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void unpack(const uint4 &v, float *f) {
+        f[0] = __uint_as_float(v.x << 16);
+        f[1] = __uint_as_float(v.x & 0xffff0000u);
+        f[2] = __uint_as_float(v.y << 16);
+        f[3] = __uint_as_float(v.y & 0xffff0000u);
+        f[4] = __uint_as_float(v.z << 16);
+        f[5] = __uint_as_float(v.z & 0xffff0000u);
+        f[6] = __uint_as_float(v.w << 16);
+        f[7] = __uint_as_float(v.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void store(char *p, const float *f) {
+        uint4 o;
+        o.x = pack_bf16x2(f[0], f[1]);
+        o.y = pack_bf16x2(f[2], f[3]);
+        o.z = pack_bf16x2(f[4], f[5]);
+        o.w = pack_bf16x2(f[6], f[7]);
+        *(uint4 *)p = o;
+    }
+};
+template <>
+struct Vec16<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void unpack(const uint4 &v, float *f) {
+        f[0] = __uint_as_float(v.x);
+        f[1] = __uint_as_float(v.y);
+        f[2] = __uint_as_float(v.z);
+        f[3] = __uint_as_float(v.w);
+    }
+    static __device__ __forceinline__ void store(char *p, const float *f) {
+        *(float4 *)p = make_float4(f[0], f[1], f[2], f[3]);
+    }
+};
+
+// out[t] = sum_j w[t,j] * staging[t*k+j] for the tokens of one task.  WAIT:
+// spin (bounded) until the flags covering the token's rows carry this call's
+// epoch; otherwise check once and report.  Flags are read with relaxed atomic
+// loads followed by one acquire fence at the requested scope.
+template <typename ET, bool WAIT>
+__device__ void combine_task(const KArgs &a, int task) {
+    using V = Vec16<ET>;
+    const int tid = threadIdx.x;
+    const int k = a.k, sys = a.fence_scope;
+    const char *staging = (const char *)a.staging;
+    const int pieces = a.d * (int)sizeof(ET) / 16;
+    for (int tt = 0; tt < a.comb_tokens; ++tt) {
+        const int t = task * a.comb_tokens + tt;
+        if (t >= a.T) break;
+        if (a.slot_flag && a.flags) {
+            bool ok = true;
+            for (int q = tid; q < k * a.ncb; q += kThreads) {
+                const u32 *fp = &a.flags[a.slot_flag[(size_t)t * k + q / a.ncb] + q % a.ncb];
+                if (WAIT) {
+                    const u64 t0 = now_ticks();
+                    int spins = 0;
+                    while (ld_relaxed(fp, sys) != a.epoch) {
+                        __builtin_amdgcn_s_sleep(2);
+                        if ((++spins & 63) == 0) {
+                            if (ld_relaxed_agent(&a.ctrl->error) != 0) break;
+                            if (now_ticks() - t0 > kWaitTicks) {
+                                set_error(a.ctrl, MOE_ERR_TIMEOUT);
+                                atomicAdd(&a.ctrl->stats[6], 1ull);
+                                break;
+                            }
+                        }
+                    }
+                } else {
+                    ok = ok && (ld_relaxed(fp, sys) == a.epoch);
+                }
+            }
+            fence_acquire(sys);
+            if (!WAIT && !ok && a.status_dev) atomicExch(a.status_dev, (int)MOE_ERR_NOT_READY);
+        }
+        __syncthreads();
+        for (int c = tid; c < pieces; c += kThreads) {
+            float acc[V::N];
+#pragma unroll
+            for (int i = 0; i < V::N; ++i) acc[i] = 0.f;
+            const char *row = staging + ((size_t)t * k * a.d) * sizeof(ET) + (size_t)c * 16;
+            const size_t rstride = (size_t)a.d * sizeof(ET);
+            int j = 0;
+            for (; j + 4 <= k; j += 4) {
+                const uint4 v0 = *(const uint4 *)(row + (size_t)j * rstride);
+                const uint4 v1 = *(const uint4 *)(row + (size_t)(j + 1) * rstride);
+                const uint4 v2 = *(const uint4 *)(row + (size_t)(j + 2) * rstride);
+                const uint4 v3 = *(const uint4 *)(row + (size_t)(j + 3) * rstride);
+                float f0[V::N], f1[V::N], f2[V::N], f3[V::N];
+                V::unpack(v0, f0);
+                V::unpack(v1, f1);
+                V::unpack(v2, f2);
+                V::unpack(v3, f3);
+                const float w0 = a.w[(size_t)t * k + j], w1 = a.w[(size_t)t * k + j + 1];
+                const float w2 = a.w[(size_t)t * k + j + 2], w3 = a.w[(size_t)t * k + j + 3];
+#pragma unroll
+                for (int i = 0; i < V::N; ++i) {
+                    acc[i] = fmaf(w0, f0[i], acc[i]);
+                    acc[i] = fmaf(w1, f1[i], acc[i]);
+                    acc[i] = fmaf(w2, f2[i], acc[i]);
+                    acc[i] = fmaf(w3, f3[i], acc[i]);
+                }
+            }
+            for (; j < k; ++j) {
+                const uint4 v0 = *(const uint4 *)(row + (size_t)j * rstride);
+                float f0[V::N];
+                V::unpack(v0, f0);
+                const float w0 = a.w[(size_t)t * k + j];
+#pragma unroll
+                for (int i = 0; i < V::N; ++i) acc[i] = fmaf(w0, f0[i], acc[i]);
+            }
+            V::store((char *)a.out + ((size_t)t * a.d) * sizeof(ET) + (size_t)c * 16, acc);
+        }
+    }
+}
+
+}  // namespace moe

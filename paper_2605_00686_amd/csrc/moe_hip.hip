@@ -1,0 +1,457 @@
+// C ABI of the MoE hot path for MI355X (gfx950): argument validation, workspace
+// layout, kernel selection and launches.  Declarations and contracts live in
+// include/moe.h.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+
+#include "common.hpp"
+#include "dispatch.hpp"
+#include "expert.hpp"
+#include "route.hpp"
+
+namespace moe {
+
+// ------------------------------------------------------------------ kernels
+__global__ __launch_bounds__(kThreads) void k_zero(u32 *p, size_t n) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = 0u;
+}
+
+template <typename ET>
+__global__ __launch_bounds__(kThreads) void k_route(KArgs a, int do_hist) {
+    extern __shared__ __align__(16) char smem[];
+    route_task<ET>(a, blockIdx.x, smem, do_hist != 0);
+}
+
+__global__ __launch_bounds__(kThreads) void k_plan(KArgs a) {
+    extern __shared__ __align__(16) char smem[];
+    plan_task(a, smem);
+}
+
+template <typename ET>
+__global__ __launch_bounds__(kThreads) void k_perm(KArgs a) {
+    extern __shared__ __align__(16) char smem[];
+    if (a.ctrl->error == 0) perm_task<ET>(a, blockIdx.x, smem);
+}
+
+__global__ __launch_bounds__(kThreads) void k_gather(KArgs a, size_t row_bytes) {
+    if (a.ctrl->error != 0) return;
+    const int wave = (blockIdx.x * kThreads + threadIdx.x) >> 6;
+    gather_rows(a, wave, (gridDim.x * kThreads) >> 6, row_bytes);
+}
+
+// standalone dispatch leaves the control block clean for the next call
+__global__ __launch_bounds__(kThreads) void k_dispatch_finish(KArgs a) {
+    u32 *z = (u32 *)a.ctrl;
+    const size_t n = a.zero_bytes / 4;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        z[i] = 0u;
+}
+
+template <typename ET>
+__global__ __launch_bounds__(kThreads) void k_combine(KArgs a) {
+    combine_task<ET, false>(a, blockIdx.x);
+}
+
+// The whole layer in one persistent kernel.  Workgroups draw task numbers from
+// one counter; the task list is ordered so that a task only ever waits for
+// lower-numbered tasks, all of which have been drawn by workgroups that are
+// already running: no wait can deadlock, whatever the grid size.
+//   [gate tasks | plan | permutation blocks | GEMM1 tiles | GEMM2 tiles | combine tasks]
+template <class P>
+__global__ __launch_bounds__(kThreads) void k_megakernel(KArgs a) {
+    using ET = typename P::ET;
+    extern __shared__ __align__(16) char smem[];
+    __shared__ int s_task, s_ok, s_last;
+    Ctrl *c = a.ctrl;
+    const int tid = threadIdx.x;
+    while (true) {
+        __syncthreads();
+        if (tid == 0) s_task = (int)atomicAdd(&c->next_task, 1u);
+        __syncthreads();
+        const int task = s_task;
+        if (task >= a.t_end) break;
+        if (task < a.t_plan) {
+            route_task<ET>(a, task, smem, true);
+            sync_stores();
+            if (tid == 0) {
+                fence_release(0);
+                atomicAdd(&c->route_done, 1u);
+            }
+        } else if (task < a.t_perm) {
+            if (tid == 0) s_ok = wait_ge(c, &c->route_done, (u32)a.nRT) ? 1 : 0;
+            __syncthreads();
+            if (s_ok) plan_task(a, smem);
+            sync_stores();
+            if (tid == 0) {
+                fence_release(0);
+                __hip_atomic_store(&c->plan_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        } else if (task < a.t_g1) {
+            if (tid == 0) s_ok = (wait_ge(c, &c->plan_done, 1u) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
+            __syncthreads();
+            if (s_ok) perm_task<ET>(a, task - a.t_perm, smem);
+            sync_stores();
+            if (tid == 0) {
+                fence_release(0);
+                atomicAdd(&c->perm_done, 1u);
+            }
+        } else if (task < a.t_g2) {
+            if (tid == 0) s_ok = (wait_ge(c, &c->perm_done, (u32)a.nPB) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
+            __syncthreads();
+            if (s_ok) g1_tile<P>(a, task - a.t_g1, smem);
+        } else if (task < a.t_comb) {
+            // plan_done is implied: this workgroup or an earlier task already waited for it,
+            // but a workgroup may arrive here without having done so -> wait again (cheap).
+            if (tid == 0) s_ok = wait_ge(c, &c->plan_done, 1u) ? 1 : 0;
+            __syncthreads();
+            TileInfo ti;
+            ti.valid = false;
+            if (s_ok) ti = decode_tile(a, task - a.t_g2, a.tl.NT2, P::BN2, a.d);
+            if (ti.valid) {  // uniform: every thread decodes the same tile
+                __syncthreads();
+                if (tid == 0)
+                    s_ok = (wait_ge(c, &a.h_ready[ti.rb], (u32)a.tl.NT1) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
+                __syncthreads();
+                if (s_ok) g2_tile<P>(a, ti, smem);
+            }
+        } else {
+            if (tid == 0) s_ok = (wait_ge(c, &c->perm_done, (u32)a.nPB) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
+            __syncthreads();
+            if (s_ok) combine_task<ET, true>(a, task - a.t_comb);
+        }
+    }
+    // last workgroup out copies the statistics and clears the control block
+    sync_stores();
+    if (tid == 0) {
+        fence_release(0);
+        const u32 old = atomicAdd(&c->exit_count, 1u);
+        s_last = (old == gridDim.x - 1) ? 1 : 0;
+        if (s_last) fence_acquire(0);
+    }
+    __syncthreads();
+    if (s_last) {
+        if (a.stats) {
+            if (tid < MOE_NUM_STATS - 1) a.stats[tid] = c->stats[tid];
+            if (tid == MOE_NUM_STATS - 1) a.stats[tid] = (u64)(long long)(-(int)c->error);
+        }
+        __syncthreads();
+        u32 *z = (u32 *)c;
+        for (size_t i = tid; i < a.zero_bytes / 4; i += kThreads) z[i] = 0u;
+    }
+}
+
+// --------------------------------------------------------------- host side
+static inline size_t align_up(size_t v, size_t al) { return (v + al - 1) / al * al; }
+
+static int elem_size(int dtype) { return dtype == MOE_DT_F32 ? 4 : 2; }
+
+enum TileKind { TK_F32 = 0, TK_L = 1, TK_M = 2, TK_S = 3 };
+
+struct Plan {
+    moe_problem_t p;
+    int tile_m, tile_n, N, per_dest, ncb, nPB, nRT, nCT, comb_tokens, maxRB_layout;
+    int kind;
+    Tiling tl;
+    // workspace byte offsets
+    size_t o_ctrl, o_blk_hist, o_seg_cnt, o_dest_counter, o_h_ready, zero_bytes;
+    size_t o_blk_base, o_seg_begin, o_flag_base, o_dest_flag_begin, o_rb_base, o_rb_expert, o_h, total;
+};
+
+static int make_plan(const moe_problem_t *p, Plan *pl) {
+    if (!p) return MOE_ERR_INVALID_ARG;
+    if (p->T < 1 || p->d < 1 || p->E < 1 || p->k < 1 || p->f < 1 || p->R < 1) return MOE_ERR_INVALID_ARG;
+    if (p->k > p->E || p->T % p->R != 0) return MOE_ERR_INVALID_ARG;
+    if (p->dtype != MOE_DT_F32 && p->dtype != MOE_DT_BF16) return MOE_ERR_INVALID_ARG;
+    if (p->signal_mode != MOE_SIGNAL_PER_TILE && p->signal_mode != MOE_SIGNAL_PER_DEST) return MOE_ERR_INVALID_ARG;
+    if (p->fence_scope != MOE_SCOPE_AGENT && p->fence_scope != MOE_SCOPE_SYSTEM) return MOE_ERR_INVALID_ARG;
+    if (p->tile_m < 0 || p->tile_n < 0) return MOE_ERR_INVALID_ARG;
+    if (p->E > kMaxExperts || p->k > 32 || p->R > kMaxDest) return MOE_ERR_UNSUPPORTED;
+    if ((long long)p->T * p->k > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
+    const int tm = p->tile_m ? p->tile_m : 128, tn = p->tile_n ? p->tile_n : 64;
+    if (tm != 32 && tm != 64 && tm != 128) return MOE_ERR_UNSUPPORTED;
+    if (tn != 64 && tn != 128) return MOE_ERR_UNSUPPORTED;
+    // 16-byte pieces everywhere; the MFMA main loop steps K by 64, the fp32 one by 16
+    const int kstep = (p->dtype == MOE_DT_BF16) ? 64 : 16;
+    if (p->d % kstep != 0 || p->f % kstep != 0) return MOE_ERR_UNSUPPORTED;
+    pl->p = *p;
+    pl->tile_m = tm;
+    pl->tile_n = tn;
+    pl->N = p->T * p->k;
+    pl->per_dest = p->T / p->R;
+    pl->ncb = (p->d + tn - 1) / tn;
+    pl->nPB = (p->T + kPermBlock - 1) / kPermBlock;
+    pl->nRT = (p->T + kRouteTokens - 1) / kRouteTokens;
+    pl->comb_tokens = (p->T >= 8192) ? 4 : 1;
+    pl->nCT = (p->T + pl->comb_tokens - 1) / pl->comb_tokens;
+    // tile shape: the smallest row block that holds an average expert, never
+    // smaller than the publish tile (a publish tile must not span two compute tiles)
+    const int avg = pl->N / p->E;
+    int bm;
+    if (p->dtype == MOE_DT_F32) {
+        pl->kind = TK_F32;
+        bm = TileF32::BM;
+        pl->tl.BN1 = TileF32::BN;
+        pl->tl.BN2 = TileF32::BN;
+    } else {
+        if (avg >= 512)
+            pl->kind = TK_L;
+        else if (avg >= 96 || tm > 32)
+            pl->kind = TK_M;
+        else
+            pl->kind = TK_S;
+        bm = pl->kind == TK_L ? CfgL::BM : pl->kind == TK_M ? CfgM::BM : CfgS::BM;
+        pl->tl.BN1 = 128;
+        pl->tl.BN2 = 256;
+    }
+    if (bm % tm != 0) return MOE_ERR_UNSUPPORTED;
+    pl->tl.BM = bm;
+    pl->tl.NT1 = (p->f + pl->tl.BN1 - 1) / pl->tl.BN1;
+    pl->tl.NT2 = (p->d + pl->tl.BN2 - 1) / pl->tl.BN2;
+    pl->tl.maxRB = pl->N / bm + p->E;
+    pl->maxRB_layout = pl->N / 32 + p->E;  // layout does not depend on the tile choice
+    if ((long long)pl->tl.maxRB * (pl->tl.NT1 + pl->tl.NT2) > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
+    size_t o = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = o;
+        o = align_up(o + bytes, 256);
+        return at;
+    };
+    pl->o_ctrl = take(sizeof(Ctrl));
+    pl->o_blk_hist = take((size_t)pl->nPB * p->E * 4);
+    pl->o_seg_cnt = take((size_t)p->E * p->R * 4);
+    pl->o_dest_counter = take((size_t)p->R * 4);
+    pl->o_h_ready = take((size_t)pl->maxRB_layout * 4);
+    pl->zero_bytes = o;
+    pl->o_blk_base = take((size_t)pl->nPB * p->E * 4);
+    pl->o_seg_begin = take((size_t)p->E * p->R * 4);
+    pl->o_flag_base = take((size_t)p->E * p->R * 4);
+    pl->o_dest_flag_begin = take((size_t)(p->R + 1) * 4);
+    pl->o_rb_base = take((size_t)(p->E + 1) * 4);
+    pl->o_rb_expert = take((size_t)pl->maxRB_layout * 4);
+    pl->o_h = take((size_t)pl->N * p->f * elem_size(p->dtype));
+    pl->total = o;
+    return MOE_OK;
+}
+
+static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
+    const moe_problem_t &p = pl.p;
+    memset(a, 0, sizeof(*a));
+    a->T = p.T; a->d = p.d; a->E = p.E; a->k = p.k; a->f = p.f; a->R = p.R;
+    a->dtype = p.dtype; a->tile_m = pl.tile_m; a->tile_n = pl.tile_n;
+    a->signal_mode = p.signal_mode; a->fence_scope = p.fence_scope; a->epoch = p.epoch;
+    a->N = pl.N; a->per_dest = pl.per_dest; a->ncb = pl.ncb;
+    a->nPB = pl.nPB; a->nRT = pl.nRT; a->nCT = pl.nCT; a->comb_tokens = pl.comb_tokens;
+    a->tl = pl.tl;
+    a->t_plan = pl.nRT;
+    a->t_perm = a->t_plan + 1;
+    a->t_g1 = a->t_perm + pl.nPB;
+    a->t_g2 = a->t_g1 + pl.tl.maxRB * pl.tl.NT1;
+    a->t_comb = a->t_g2 + pl.tl.maxRB * pl.tl.NT2;
+    a->t_end = a->t_comb + pl.nCT;
+    char *ws = (char *)workspace;
+    if (ws) {
+        a->ctrl = (Ctrl *)(ws + pl.o_ctrl);
+        a->blk_hist = (int32_t *)(ws + pl.o_blk_hist);
+        a->seg_cnt = (int32_t *)(ws + pl.o_seg_cnt);
+        a->dest_counter = (u32 *)(ws + pl.o_dest_counter);
+        a->h_ready = (u32 *)(ws + pl.o_h_ready);
+        a->blk_base = (int32_t *)(ws + pl.o_blk_base);
+        a->seg_begin = (int32_t *)(ws + pl.o_seg_begin);
+        a->flag_base = (int32_t *)(ws + pl.o_flag_base);
+        a->dest_flag_begin = (int32_t *)(ws + pl.o_dest_flag_begin);
+        a->rb_base = (int32_t *)(ws + pl.o_rb_base);
+        a->rb_expert = (int32_t *)(ws + pl.o_rb_expert);
+        a->h = ws + pl.o_h;
+        a->zero_bytes = pl.zero_bytes;
+    }
+}
+
+static size_t plan_smem(const Plan &pl) { return (size_t)(3 * pl.p.E + pl.p.R + 8) * 4; }
+
+static int check_ws(const void *ws) {
+    if (!ws || ((uintptr_t)ws & 255u)) return MOE_ERR_WORKSPACE;
+    return MOE_OK;
+}
+
+static int hip_ok(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_HIP; }
+
+template <class K>
+static int set_smem(K kernel, size_t bytes) {
+    if (bytes > 160 * 1024) return MOE_ERR_UNSUPPORTED;
+    if (bytes > 48 * 1024)
+        return hip_ok(hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    return MOE_OK;
+}
+
+template <class P>
+static int launch_mega(const Plan &pl, const KArgs &a, hipStream_t st) {
+    size_t smem = tile_smem_bytes<P>();
+    if (a.Wg && route_smem_bytes(pl.p.E) > smem) smem = route_smem_bytes(pl.p.E);
+    if (plan_smem(pl) > smem) smem = plan_smem(pl);
+    auto kern = k_megakernel<P>;
+    int rc = set_smem(kern, smem);
+    if (rc) return rc;
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return MOE_ERR_HIP;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kThreads, smem) != hipSuccess) return MOE_ERR_HIP;
+    if (per_cu < 1) return MOE_ERR_UNSUPPORTED;
+    if (per_cu > 2) per_cu = 2;
+    long long grid = (long long)cus * per_cu;
+    if (grid > a.t_end) grid = a.t_end;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), smem, st, a);
+    return hip_ok(hipGetLastError());
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+const char *moe_status_string(int s) {
+    switch (s) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_INVALID_ARG: return "invalid argument";
+        case MOE_ERR_UNSUPPORTED: return "unsupported problem";
+        case MOE_ERR_WORKSPACE: return "workspace missing or misaligned";
+        case MOE_ERR_NOT_READY: return "a ready flag was not at the expected epoch";
+        case MOE_ERR_HIP: return "HIP runtime error";
+        case MOE_ERR_TIMEOUT: return "a bounded in-kernel wait expired";
+        case MOE_ERR_BAD_ROUTING: return "expert id outside [0, E)";
+        default: return "unknown status";
+    }
+}
+
+size_t moe_workspace_bytes(const moe_problem_t *p) {
+    Plan pl;
+    if (make_plan(p, &pl) != MOE_OK) return 0;
+    return pl.total;
+}
+
+size_t moe_num_flags(const moe_problem_t *p) {
+    Plan pl;
+    if (make_plan(p, &pl) != MOE_OK) return 0;
+    // a segment of c rows touches at most c/tile_m + 1 row blocks; there are E*R segments
+    return ((size_t)(pl.N + pl.tile_m - 1) / pl.tile_m + (size_t)p->E * p->R) * pl.ncb;
+}
+
+int moe_workspace_init(const moe_problem_t *p, void *workspace, void *stream) {
+    Plan pl;
+    int rc = make_plan(p, &pl);
+    if (rc) return rc;
+    if ((rc = check_ws(workspace))) return rc;
+    hipLaunchKernelGGL(k_zero, dim3(64), dim3(kThreads), 0, (hipStream_t)stream, (u32 *)workspace, pl.zero_bytes / 4);
+    return hip_ok(hipGetLastError());
+}
+
+int moe_route(const moe_problem_t *p, const void *x, const void *Wg, const float *gate_bias, int32_t *topk_idx,
+              float *topk_w, void *stream) {
+    Plan pl;
+    int rc = make_plan(p, &pl);
+    if (rc) return rc;
+    if (!x || !Wg || !topk_idx || !topk_w) return MOE_ERR_INVALID_ARG;
+    KArgs a;
+    fill_args(pl, nullptr, &a);
+    a.x = x; a.Wg = Wg; a.bias = gate_bias; a.idx = topk_idx; a.w = topk_w;
+    const size_t smem = route_smem_bytes(p->E);
+    hipStream_t st = (hipStream_t)stream;
+    if (p->dtype == MOE_DT_F32) {
+        if ((rc = set_smem(k_route<float>, smem))) return rc;
+        hipLaunchKernelGGL(k_route<float>, dim3(pl.nRT), dim3(kThreads), smem, st, a, 0);
+    } else {
+        if ((rc = set_smem(k_route<bf16_t>, smem))) return rc;
+        hipLaunchKernelGGL(k_route<bf16_t>, dim3(pl.nRT), dim3(kThreads), smem, st, a, 0);
+    }
+    return hip_ok(hipGetLastError());
+}
+
+int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx, int32_t *counts, int32_t *offsets,
+                 int32_t *perm, int32_t *inv_perm, void *x_perm, void *workspace, void *stream) {
+    Plan pl;
+    int rc = make_plan(p, &pl);
+    if (rc) return rc;
+    if (!topk_idx || !counts || !offsets || !perm || !inv_perm) return MOE_ERR_INVALID_ARG;
+    if (x_perm && !x) return MOE_ERR_INVALID_ARG;
+    if ((rc = check_ws(workspace))) return rc;
+    KArgs a;
+    fill_args(pl, workspace, &a);
+    a.x = x; a.idx = const_cast<int32_t *>(topk_idx);
+    a.counts = counts; a.offsets = offsets; a.perm = perm; a.inv_perm = inv_perm; a.x_perm = x_perm;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t psmem = plan_smem(pl);
+    if ((rc = set_smem(k_plan, psmem))) return rc;
+    // histogram (gate task without the gate), plan, permutation, row gather, clean-up
+    if (p->dtype == MOE_DT_F32) {
+        hipLaunchKernelGGL(k_route<float>, dim3(pl.nRT), dim3(kThreads), 0, st, a, 1);
+        hipLaunchKernelGGL(k_plan, dim3(1), dim3(kThreads), psmem, st, a);
+        hipLaunchKernelGGL(k_perm<float>, dim3(pl.nPB), dim3(kThreads), (size_t)p->E * 8, st, a);
+    } else {
+        hipLaunchKernelGGL(k_route<bf16_t>, dim3(pl.nRT), dim3(kThreads), 0, st, a, 1);
+        hipLaunchKernelGGL(k_plan, dim3(1), dim3(kThreads), psmem, st, a);
+        hipLaunchKernelGGL(k_perm<bf16_t>, dim3(pl.nPB), dim3(kThreads), (size_t)p->E * 8, st, a);
+    }
+    if (x_perm) {
+        const size_t row_bytes = (size_t)p->d * elem_size(p->dtype);
+        int grid = (pl.N + 3) / 4;  // one wavefront per row while rows last
+        if (grid > 8192) grid = 8192;
+        hipLaunchKernelGGL(k_gather, dim3(grid), dim3(kThreads), 0, st, a, row_bytes);
+    }
+    hipLaunchKernelGGL(k_dispatch_finish, dim3(16), dim3(kThreads), 0, st, a);
+    return hip_ok(hipGetLastError());
+}
+
+int moe_megakernel_forward(const moe_problem_t *p, const void *x, const void *Wg, const float *gate_bias,
+                           const void *W1, const void *W3, const void *W2, int32_t *topk_idx, float *topk_w,
+                           int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm, int32_t *slot_flag,
+                           void *staging, uint32_t *flags, void *out, uint64_t *stats, void *workspace,
+                           void *stream) {
+    Plan pl;
+    int rc = make_plan(p, &pl);
+    if (rc) return rc;
+    if (!x || !W1 || !W3 || !W2 || !topk_idx || !topk_w || !counts || !offsets || !perm || !inv_perm || !slot_flag ||
+        !staging || !flags || !out)
+        return MOE_ERR_INVALID_ARG;
+    if (p->epoch == 0) return MOE_ERR_INVALID_ARG;
+    if ((rc = check_ws(workspace))) return rc;
+    KArgs a;
+    fill_args(pl, workspace, &a);
+    a.x = x; a.Wg = Wg; a.bias = gate_bias; a.W1 = W1; a.W3 = W3; a.W2 = W2;
+    a.idx = topk_idx; a.w = topk_w; a.counts = counts; a.offsets = offsets; a.perm = perm; a.inv_perm = inv_perm;
+    a.slot_flag = slot_flag; a.staging = staging; a.flags = flags; a.out = out;
+    a.stats = (u64 *)stats;
+    hipStream_t st = (hipStream_t)stream;
+    switch (pl.kind) {
+        case TK_F32: return launch_mega<F32Policy>(pl, a, st);
+        case TK_L: return launch_mega<Bf16Policy<CfgL>>(pl, a, st);
+        case TK_M: return launch_mega<Bf16Policy<CfgM>>(pl, a, st);
+        default: return launch_mega<Bf16Policy<CfgS>>(pl, a, st);
+    }
+}
+
+int moe_combine(const moe_problem_t *p, const void *staging, const uint32_t *flags, const int32_t *slot_flag,
+                const float *topk_w, void *out, int32_t *status_dev, void *stream) {
+    Plan pl;
+    int rc = make_plan(p, &pl);
+    if (rc) return rc;
+    if (!staging || !topk_w || !out) return MOE_ERR_INVALID_ARG;
+    if ((slot_flag != nullptr) != (flags != nullptr)) return MOE_ERR_INVALID_ARG;
+    KArgs a;
+    fill_args(pl, nullptr, &a);
+    a.staging = const_cast<void *>(staging);
+    a.flags = const_cast<uint32_t *>(flags);
+    a.slot_flag = const_cast<int32_t *>(slot_flag);
+    a.w = const_cast<float *>(topk_w);
+    a.out = out;
+    a.status_dev = status_dev;
+    hipStream_t st = (hipStream_t)stream;
+    if (p->dtype == MOE_DT_F32)
+        hipLaunchKernelGGL(k_combine<float>, dim3(pl.nCT), dim3(kThreads), 0, st, a);
+    else
+        hipLaunchKernelGGL(k_combine<bf16_t>, dim3(pl.nCT), dim3(kThreads), 0, st, a);
+    return hip_ok(hipGetLastError());
+}
+
+}  // extern "C"

@@ -35,6 +35,7 @@ CONFIGS = {
     "mini_skew": dict(T=512, d=256, E=16, k=4, f=384, R=8, dtype="bf16", seed=13, bias_std=1.5),
     "mini_pre": dict(T=640, d=512, E=4, k=1, f=256, R=16, dtype="bf16", seed=14,
                      prerouted=dict(global_experts=256, zipf=1.1, topk=8)),
+    "mini_large": dict(T=2048, d=512, E=4, k=2, f=384, R=8, dtype="bf16", seed=16),
     "mini_decode": dict(T=64, d=1024, E=16, k=4, f=512, R=32, dtype="bf16", seed=15, tile_m=32),
 }
 

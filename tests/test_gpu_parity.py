@@ -1,0 +1,237 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Sizes here finish in seconds on the CPU yet span
+several tiles, ragged tails, empty segments and both signaling modes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_00686_amd import workloads as W
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _binding():
+    from paper_2605_00686_amd import binding as B
+    return B
+
+
+def _dev(inp, names):
+    return {n: (inp[n].cuda() if inp.get(n) is not None else None) for n in names}
+
+
+def _problem(B, cfg, signal_mode=1, fence_scope=0, epoch=1):
+    return B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
+                     tile_n=cfg["tile_n"], signal_mode=signal_mode, fence_scope=fence_scope, epoch=epoch)
+
+
+def run_forward(B, inp, signal_mode, fence_scope, epoch=1, buf=None):
+    cfg = inp["cfg"]
+    p = _problem(B, cfg, signal_mode, fence_scope, epoch)
+    buf = buf or B.Buffers(p)
+    d = _dev(inp, ("x", "Wg", "gate_bias", "W1", "W3", "W2"))
+    if cfg["prerouted"] is not None:
+        buf.topk_idx.copy_(inp["topk_idx"])
+        buf.topk_w.copy_(inp["topk_w"])
+    buf.staging.fill_(float("nan"))  # poison: a row read before its flag would show
+    buf.out.fill_(float("nan"))
+    B.forward(p, buf, d["x"], d["Wg"], d["gate_bias"], d["W1"], d["W3"], d["W2"])
+    torch.cuda.synchronize()
+    return p, buf
+
+
+def check_against_oracle(B, inp, p, buf, signal_mode, ref=None):
+    cfg = inp["cfg"]
+    o = parity.oracle_arrays(inp)
+    idx, w, margin = parity.oracle_routing(inp)
+    if ref is None:
+        ref = oracle.forward(o["x"], o["Wg"], o["W1"], o["W3"], o["W2"], cfg["k"], idx=idx, w=w)
+    stats = buf.stats.cpu().numpy()
+    assert stats[7] == 0, f"device status {stats[7]} ({B.status_string(int(stats[7]))}), timeouts {stats[6]}"
+    # integer work: bit-exact
+    assert np.array_equal(buf.topk_idx.cpu().numpy(), idx), f"routing differs (min margin {None if margin is None else margin.min()})"
+    np.testing.assert_allclose(buf.topk_w.cpu().numpy(), w, rtol=1e-5, atol=1e-7)
+    assert np.array_equal(buf.counts.cpu().numpy(), ref["counts"])
+    assert np.array_equal(buf.offsets.cpu().numpy(), ref["offsets"])
+    assert np.array_equal(buf.perm.cpu().numpy(), ref["perm"])
+    assert np.array_equal(buf.inv_perm.cpu().numpy(), ref["inv_perm"])
+    plan = oracle.publish_plan(idx, ref["offsets"], ref["inv_perm"], cfg["E"], cfg["R"], cfg["d"], cfg["tile_m"],
+                               cfg["tile_n"])
+    assert np.array_equal(buf.slot_flag.cpu().numpy(), plan["slot_flag"])
+    nfl = plan["n_flags"]
+    assert nfl <= B.moe_num_flags(p)
+    flags = buf.flags.cpu().numpy().view(np.uint32)
+    assert np.all(flags[:nfl] == p.epoch), "a published tile has no flag"
+    assert stats[0] == parity.expected_fences(plan, signal_mode), (stats, plan["fences_per_tile"], plan["fences_per_dest"])
+    assert stats[1] == nfl and stats[2] == nfl
+    # floating point
+    is_f32 = cfg["dtype"] == "f32"
+    faithful = None
+    if not is_f32:
+        faithful = oracle.forward(o["x"], o["Wg"], o["W1"], o["W3"], o["W2"], cfg["k"], idx=idx, w=w, faithful=True)
+    st = buf.staging.float().cpu().numpy()
+    out = buf.out.float().cpu().numpy()
+    assert not np.isnan(st).any() and not np.isnan(out).any(), "poison survived: a row was never written"
+    m1 = parity.check_outputs("staging", st, ref["staging"], None if faithful is None else faithful["staging"], is_f32)
+    m2 = parity.check_outputs("out", out, ref["out"], None if faithful is None else faithful["out"], is_f32)
+    print(f"[{cfg}] staging {m1} out {m2} stats {stats.tolist()}")
+    return ref
+
+
+@pytest.mark.parametrize("name", ["mini_f32", "mini_bf16", "mini_skew", "mini_pre", "mini_decode", "mini_large"])
+@pytest.mark.parametrize("signal_mode", [0, 1])
+def test_megakernel_parity(name, signal_mode):
+    B = _binding()
+    print(f"case {name} signal_mode {signal_mode}", flush=True)
+    inp = W.make_inputs(name)
+    p, buf = run_forward(B, inp, signal_mode, 0)
+    check_against_oracle(B, inp, p, buf, signal_mode)
+
+
+def test_megakernel_system_scope_and_reuse():
+    """Same buffers, three calls in a row with rising epochs, both scopes and
+    both modes: the workspace must come back clean each time."""
+    B = _binding()
+    inp = W.make_inputs("mini_skew")
+    print("case mini_skew reuse", flush=True)
+    ref, buf = None, None
+    for epoch, (mode, scope) in enumerate([(1, 1), (0, 1), (1, 0), (0, 0)], start=3):
+        p, buf = run_forward(B, inp, mode, scope, epoch=epoch, buf=buf)
+        ref = check_against_oracle(B, inp, p, buf, mode, ref)
+
+
+@pytest.mark.parametrize("name", ["mini_f32", "mini_bf16", "mini_skew", "mini_decode"])
+def test_route_parity(name):
+    B = _binding()
+    print(f"case route {name}", flush=True)
+    inp = W.make_inputs(name, with_weights=False)
+    cfg = inp["cfg"]
+    p = _problem(B, cfg)
+    d = _dev(inp, ("x", "Wg", "gate_bias"))
+    idx = torch.empty((cfg["T"], cfg["k"]), dtype=torch.int32, device="cuda")
+    w = torch.empty((cfg["T"], cfg["k"]), dtype=torch.float32, device="cuda")
+    B.moe_route(p, d["x"], d["Wg"], d["gate_bias"], idx, w)
+    torch.cuda.synchronize()
+    ridx, rw, margin = parity.oracle_routing(inp)
+    assert np.array_equal(idx.cpu().numpy(), ridx), f"min margin {margin.min()}"
+    np.testing.assert_allclose(w.cpu().numpy(), rw, rtol=1e-5, atol=1e-7)
+    s = w.cpu().numpy().astype(np.float64).sum(axis=1)
+    assert np.abs(s - 1).max() < 1e-6
+    assert all(len(set(r)) == cfg["k"] for r in idx.cpu().numpy().tolist())
+
+
+def test_route_equal_logits_tie_break():
+    """All logits equal: the k lowest expert ids, weights 1/k (degenerate case)."""
+    B = _binding()
+    T, d, E, k = 32, 64, 12, 3
+    p = B.problem(T, d, E, k, 64, 1, "bf16")
+    x = torch.zeros((T, d), dtype=torch.bfloat16, device="cuda")
+    Wg = torch.randn((d, E), device="cuda").to(torch.bfloat16)
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    w = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    B.moe_route(p, x, Wg, None, idx, w)
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), np.tile(np.arange(k, dtype=np.int32), (T, 1)))
+    np.testing.assert_allclose(w.cpu().numpy(), 1.0 / k, rtol=1e-6)
+
+
+@pytest.mark.parametrize("name", ["mini_f32", "mini_bf16", "mini_skew", "mini_pre", "mini_decode"])
+def test_dispatch_parity(name):
+    B = _binding()
+    print(f"case dispatch {name}", flush=True)
+    inp = W.make_inputs(name, with_weights=False)
+    cfg = inp["cfg"]
+    p = _problem(B, cfg)
+    ridx, _, _ = parity.oracle_routing(inp)
+    buf = B.Buffers(p)
+    x = inp["x"].cuda()
+    idx = torch.from_numpy(ridx).cuda()
+    x_perm = torch.full((cfg["T"] * cfg["k"], cfg["d"]), float("nan"), dtype=x.dtype, device="cuda")
+    for rep in range(2):  # twice: the workspace must be reusable
+        B.moe_dispatch(p, x, idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, x_perm, buf.workspace)
+        torch.cuda.synchronize()
+        counts, offsets, perm, inv = oracle.dispatch(ridx, cfg["E"])
+        assert np.array_equal(buf.counts.cpu().numpy(), counts)
+        assert np.array_equal(buf.offsets.cpu().numpy(), offsets)
+        assert np.array_equal(buf.perm.cpu().numpy(), perm)
+        assert np.array_equal(buf.inv_perm.cpu().numpy(), inv)
+        ref_xp = oracle.gather(W.as_oracle_array(inp["x"]), perm, cfg["k"])
+        assert np.array_equal(W.as_oracle_array(x_perm), ref_xp)  # byte-exact row copy
+    # indices only
+    B.moe_dispatch(p, None, idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, None, buf.workspace)
+    torch.cuda.synchronize()
+    assert np.array_equal(buf.perm.cpu().numpy(), perm)
+
+
+def test_dispatch_empty_experts():
+    """Every token picks experts 2 and 5 only: six experts stay empty."""
+    B = _binding()
+    T, d, E, k = 100, 64, 8, 2
+    p = B.problem(T, d, E, k, 64, 4, "bf16")
+    buf = B.Buffers(p)
+    ridx = np.tile(np.array([[5, 2]], np.int32), (T, 1))
+    B.moe_dispatch(p, None, torch.from_numpy(ridx).cuda(), buf.counts, buf.offsets, buf.perm, buf.inv_perm, None,
+                   buf.workspace)
+    torch.cuda.synchronize()
+    counts, offsets, perm, inv = oracle.dispatch(ridx, E)
+    assert np.array_equal(buf.counts.cpu().numpy(), counts)
+    assert np.array_equal(buf.offsets.cpu().numpy(), offsets)
+    assert np.array_equal(buf.perm.cpu().numpy(), perm)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_combine_identity_experts_return_x(dtype):
+    """Every chosen expert returns the token itself => out = x (combine alone)."""
+    B = _binding()
+    T, d, E, k = 192, 512, 8, 4
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    p = B.problem(T, d, E, k, 64, 4, dtype)
+    g = torch.Generator().manual_seed(5)
+    x = torch.randn((T, d), generator=g).to(tdt)
+    wraw = torch.rand((T, k), generator=g) + 0.1
+    w = (wraw / wraw.sum(dim=1, keepdim=True)).float()
+    staging = x.repeat_interleave(k, dim=0).contiguous()
+    out = torch.empty((T, d), dtype=tdt, device="cuda")
+    B.moe_combine(p, staging.cuda(), None, None, w.cuda(), out, None)
+    torch.cuda.synchronize()
+    ref = oracle.combine(staging.float().numpy(), w.numpy())
+    got = out.float().cpu().numpy()
+    tol = 1e-6 if dtype == "f32" else 2.0 ** -8
+    assert np.abs(got - ref).max() <= tol * np.abs(ref).max()
+    assert np.abs(got - x.float().numpy()).max() <= (2e-6 if dtype == "f32" else 2.0 ** -7) * np.abs(ref).max()
+
+
+def test_combine_reports_missing_flag():
+    B = _binding()
+    T, d, E, k = 64, 256, 4, 2
+    p = B.problem(T, d, E, k, 64, 2, "bf16", epoch=9)
+    ncb = d // 64
+    staging = torch.zeros((T * k, d), dtype=torch.bfloat16, device="cuda")
+    w = torch.full((T, k), 0.5, device="cuda")
+    out = torch.empty((T, d), dtype=torch.bfloat16, device="cuda")
+    slot_flag = (torch.arange(T * k, dtype=torch.int32, device="cuda") * ncb).contiguous()
+    flags = torch.full((T * k * ncb,), 9, dtype=torch.int32, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.moe_combine(p, staging, flags, slot_flag, w, out, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    flags[37] = 8  # one tile of the previous epoch
+    B.moe_combine(p, staging, flags, slot_flag, w, out, status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == B.MOE_ERR_NOT_READY
+
+
+def test_bad_routing_is_reported_not_followed():
+    """An expert id outside [0, E) in precomputed routing: device status says
+    so and nothing is written out of bounds (the call still terminates)."""
+    B = _binding()
+    inp = W.make_inputs("mini_pre")
+    inp["topk_idx"] = inp["topk_idx"].clone()
+    inp["topk_idx"][17, 0] = 99
+    p, buf = run_forward(B, inp, 1, 0)
+    assert int(buf.stats.cpu().numpy()[7]) == B.MOE_ERR_BAD_ROUTING
+    # the workspace is clean again: a good call right after works
+    good = W.make_inputs("mini_pre")
+    p, buf = run_forward(B, good, 1, 0, epoch=2, buf=buf)
+    check_against_oracle(B, good, p, buf, 1)
