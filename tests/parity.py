@@ -2,12 +2,22 @@
 the HIP path on the same tensors, and compare to the stated bars.
 
 Bars (the target statement of this build): routing indices, counts, offsets,
-permutation, flag numbering and fence counts bit-exact; bf16 outputs within max
-relative error 2e-2 with an absolute floor of 1e-3 against the exact oracle,
-read per row (error normalised by the row's largest magnitude), plus the
-paper's own criterion (section 6.2 "Correctness"): fewer than 1% of elements
-outside |g - r| <= max(1e-3, 2e-2 |r|); against the bf16-faithful oracle the
-row-normalised error shrinks to a few bf16 ulps.  fp32 problems: 1e-4.
+permutation, flag numbering and fence counts bit-exact.  bf16 outputs:
+
+ (i)  against the exact (fp64-accumulating) oracle: max relative error 2e-2 with
+      an absolute floor of 1e-3, read per row: max_n |g - r| / max(max_n |r|, 1e-3).
+ (ii) the paper's criterion (section 6.2 "Correctness": error rate below 1%),
+      element by element, |g - r| <= max(1e-3, 2e-2 |r|), against the
+      bf16-faithful oracle (same arithmetic, h / y / out rounded to bf16 where
+      a bf16 MFMA pipeline must round): fewer than 0.1% of elements outside.
+      Against the exact oracle the same count is only reported and bounded by
+      8%: h has to be rounded to bf16 to become an MFMA operand, which alone
+      puts an error of about 1.5e-3 rms(y) on every y; an element then misses a
+      2% RELATIVE bound whenever |r| < 0.07 rms(y), i.e. for about 5% of
+      Gaussian-distributed outputs, whatever the kernel does.
+ (iii) against the bf16-faithful oracle the row-normalised error is at most two
+      bf16 ulps of the row maximum (8e-3).
+fp32 problems: row-normalised 1e-4.
 """
 from __future__ import annotations
 
@@ -16,7 +26,8 @@ import numpy as np
 import oracle
 from paper_2605_00686_amd import workloads as W
 
-REL, ABS_FLOOR, RATE = 2e-2, 1e-3, 0.01
+REL, ABS_FLOOR = 2e-2, 1e-3
+RATE_FAITHFUL, RATE_EXACT = 1e-3, 0.08
 REL_F32 = 1e-4
 FAITHFUL_REL = 8e-3  # two bf16 ulps of the row maximum (2 * 2^-8)
 
@@ -54,10 +65,13 @@ def check_outputs(name, got, ref, ref_faithful, is_f32):
         assert m["row_err"] <= REL_F32, f"{name}: fp32 row error {m['row_err']:.3e}"
         return m
     assert m["row_err"] <= REL, f"{name}: row-normalised error {m['row_err']:.3e} > {REL}"
-    assert m["viol_rate"] < RATE, f"{name}: {m['viol_rate']:.4%} of elements outside tolerance"
+    assert m["viol_rate"] < RATE_EXACT, f"{name}: {m['viol_rate']:.4%} of elements outside tolerance (exact oracle)"
     if ref_faithful is not None:
         m["row_err_faithful"] = float(row_err(got, ref_faithful).max())
+        m["viol_rate_faithful"] = violation_rate(got, ref_faithful)
         assert m["row_err_faithful"] <= FAITHFUL_REL, f"{name}: vs bf16-faithful oracle {m['row_err_faithful']:.3e}"
+        assert m["viol_rate_faithful"] < RATE_FAITHFUL, \
+            f"{name}: {m['viol_rate_faithful']:.4%} of elements outside tolerance (bf16-faithful oracle)"
     return m
 
 

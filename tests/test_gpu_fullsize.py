@@ -1,0 +1,94 @@
+"""GPU parity at the full sizes of the five workloads, in the launch
+configuration bench.py times.  Integer results (routing, histogram, permutation,
+flag numbering, fence counts) are compared in full; floating-point outputs are
+compared on sampled tokens the oracle computes one by one (all tokens for the
+fp32 toy layer)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2605_00686_amd import workloads as W
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+SAMPLES = {"cfg1": 256, "cfg2": 48, "cfg3": 48, "cfg4": 12, "cfg5": 24}
+
+
+def _run(name, signal_mode, fence_scope, inp=None, buf=None, epoch=1):
+    from paper_2605_00686_amd import binding as B
+    inp = inp or W.make_inputs(name)
+    cfg = inp["cfg"]
+    p = B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
+                  tile_n=cfg["tile_n"], signal_mode=signal_mode, fence_scope=fence_scope, epoch=epoch)
+    buf = buf or B.Buffers(p)
+    dev = inp.setdefault("_dev", {n: (inp[n].cuda() if inp[n] is not None else None)
+                                  for n in ("x", "Wg", "gate_bias", "W1", "W3", "W2")})
+    if cfg["prerouted"] is not None:
+        buf.topk_idx.copy_(inp["topk_idx"])
+        buf.topk_w.copy_(inp["topk_w"])
+    buf.staging.fill_(float("nan"))
+    buf.out.fill_(float("nan"))
+    B.forward(p, buf, dev["x"], dev["Wg"], dev["gate_bias"], dev["W1"], dev["W3"], dev["W2"])
+    torch.cuda.synchronize()
+    return B, inp, p, buf
+
+
+def _check(B, inp, p, buf, signal_mode, name, cache):
+    cfg = inp["cfg"]
+    stats = buf.stats.cpu().numpy()
+    assert stats[7] == 0, f"device status {stats[7]} ({B.status_string(int(stats[7]))})"
+    if "ref" not in cache:
+        o = parity.oracle_arrays(inp)
+        idx, w, margin = parity.oracle_routing(inp)
+        counts, offsets, perm, inv = oracle.dispatch(idx, cfg["E"])
+        plan = oracle.publish_plan(idx, offsets, inv, cfg["E"], cfg["R"], cfg["d"], cfg["tile_m"], cfg["tile_n"])
+        tok = W.sample_tokens(cfg, SAMPLES[name])
+        st, out = oracle.forward_tokens(o["x"], o["W1"], o["W3"], o["W2"], idx, w, tok)
+        stf = outf = None
+        if cfg["dtype"] != "f32":
+            stf, outf = oracle.forward_tokens(o["x"], o["W1"], o["W3"], o["W2"], idx, w, tok, faithful=True)
+        cache["ref"] = dict(idx=idx, w=w, margin=margin, counts=counts, offsets=offsets, perm=perm, inv=inv, plan=plan,
+                            tok=tok, st=st, out=out, stf=stf, outf=outf)
+    r = cache["ref"]
+    mm = None if r["margin"] is None else float(r["margin"].min())
+    assert np.array_equal(buf.topk_idx.cpu().numpy(), r["idx"]), f"routing differs; min margin {mm}"
+    np.testing.assert_allclose(buf.topk_w.cpu().numpy(), r["w"], rtol=1e-5, atol=1e-7)
+    assert np.array_equal(buf.counts.cpu().numpy(), r["counts"])
+    assert np.array_equal(buf.offsets.cpu().numpy(), r["offsets"])
+    assert np.array_equal(buf.perm.cpu().numpy(), r["perm"])
+    assert np.array_equal(buf.inv_perm.cpu().numpy(), r["inv"])
+    plan = r["plan"]
+    assert np.array_equal(buf.slot_flag.cpu().numpy(), plan["slot_flag"])
+    nfl = plan["n_flags"]
+    flags = buf.flags.cpu().numpy().view(np.uint32)
+    assert nfl <= flags.size and np.all(flags[:nfl] == p.epoch)
+    assert stats[0] == parity.expected_fences(plan, signal_mode)
+    assert stats[1] == nfl and stats[2] == nfl
+    # properties that hold at any size: nothing left unwritten, weights sum to one
+    k, d = cfg["k"], cfg["d"]
+    assert not torch.isnan(buf.staging).any().item() and not torch.isnan(buf.out).any().item()
+    tok = torch.from_numpy(r["tok"]).cuda().long()
+    got_out = buf.out[tok].float().cpu().numpy()
+    rows = (tok[:, None] * k + torch.arange(k, device="cuda")[None, :]).reshape(-1)
+    got_st = buf.staging[rows].float().cpu().numpy()
+    is_f32 = cfg["dtype"] == "f32"
+    m1 = parity.check_outputs("staging", got_st, r["st"], r["stf"], is_f32)
+    m2 = parity.check_outputs("out", got_out, r["out"], r["outf"], is_f32)
+    print(f"{name} mode {signal_mode}: min margin {mm} staging {m1} out {m2} stats {stats.tolist()}", flush=True)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg5", "cfg4"])
+def test_fullsize_parity(name):
+    print(f"case full-size {name}", flush=True)
+    cache = {}
+    B, inp, p, buf = _run(name, 1, 0)
+    _check(B, inp, p, buf, 1, name, cache)
+    # the coupled mode on the same buffers (workspace reuse at full size)
+    B, inp, p, buf = _run(name, 0, 0, inp=inp, buf=buf, epoch=2)
+    _check(B, inp, p, buf, 0, name, cache)
+    if name == "cfg5":  # signaling stress: both scopes as well
+        for epoch, (mode, scope) in enumerate([(1, 1), (0, 1)], start=3):
+            B, inp, p, buf = _run(name, mode, scope, inp=inp, buf=buf, epoch=epoch)
+            _check(B, inp, p, buf, mode, name, cache)
