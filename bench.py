@@ -141,9 +141,12 @@ def main():
                  "frac": flops / (avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF, "flops": flops},
         "signaling": {"fences": stats[0], "flags": stats[1], "publish_tiles": stats[2], "writer_releases": stats[3],
                       "gemm1_tiles": stats[4], "gemm2_tiles": stats[5]},
+        "timeline_us": {"gate_end": stats[8] / 1e3, "plan_end": stats[9] / 1e3, "perm_end": stats[10] / 1e3,
+                        "gemm1_end": stats[11] / 1e3, "gemm2_end": stats[12] / 1e3, "combine_end": stats[13] / 1e3,
+                        "wait_sum": stats[14] / 1e3, "workgroups": stats[15]},
     }
     if not args.no_cpu:
-        n_cpu = args.cpu_tokens or max(16, min(cfg["T"], int(8e10 / (cfg["k"] * 3 * cfg["d"] * cfg["f"]))))
+        n_cpu = args.cpu_tokens or max(16, min(cfg["T"], int(4e11 / (cfg["k"] * 3 * cfg["d"] * cfg["f"]))))
         res["cpu_baseline"] = cpu_baseline(inp, n_cpu)
     print(json.dumps(res))
 

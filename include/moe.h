@@ -75,12 +75,17 @@ typedef struct {
 } moe_problem_t;
 
 /* number of 64-bit counters moe_megakernel_forward writes to `stats` */
-#define MOE_NUM_STATS 8
+#define MOE_NUM_STATS 16
 /* stats[0] release fences issued right before flag stores (per tile, or per destination)
  * stats[1] flags stored                 stats[2] publish tiles written
  * stats[3] per-compute-tile releases that only feed a destination counter (PER_DEST)
  * stats[4] GEMM1 compute tiles          stats[5] GEMM2 compute tiles
- * stats[6] bounded waits that expired   stats[7] device status (a moe_status_t, 0 = ok) */
+ * stats[6] bounded waits that expired   stats[7] device status (a moe_status_t, 0 = ok)
+ * stats[8..13] in-kernel timeline: nanoseconds from the first task drawn to the end of
+ *   the last gate task [8], the plan [9], the last permutation block [10], the last
+ *   GEMM1 tile [11], the last GEMM2 tile [12], the last combine task [13]
+ * stats[14] nanoseconds workgroups spent waiting on dependencies, summed over workgroups
+ * stats[15] workgroups launched */
 
 /* Host, pure: bytes of workspace a problem needs / upper bound on the number
  * of flags (uint32 each) the caller must provide; 0 if the problem is invalid. */

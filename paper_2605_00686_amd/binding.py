@@ -18,7 +18,7 @@ MOE_ERR_NOT_READY, MOE_ERR_HIP, MOE_ERR_TIMEOUT, MOE_ERR_BAD_ROUTING = -4, -5, -
 MOE_DT_F32, MOE_DT_BF16 = 0, 1
 MOE_SIGNAL_PER_TILE, MOE_SIGNAL_PER_DEST = 0, 1
 MOE_SCOPE_AGENT, MOE_SCOPE_SYSTEM = 0, 1
-MOE_NUM_STATS = 8
+MOE_NUM_STATS = 16
 
 EXPORTS = ("moe_workspace_bytes", "moe_num_flags", "moe_status_string", "moe_workspace_init", "moe_route",
            "moe_dispatch", "moe_megakernel_forward", "moe_combine")

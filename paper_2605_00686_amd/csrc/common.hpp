@@ -31,6 +31,7 @@ struct Ctrl {
     u32 n_rb;        // row blocks in use (all experts)
     u32 n_flags;     // publish tiles / flags in use
     u32 pad[8];
+    u64 t0;          // wall-clock tick of the first task drawn
     u64 stats[MOE_NUM_STATS];
 };
 
@@ -135,20 +136,32 @@ __device__ __forceinline__ bool wait_ge(Ctrl *c, const u32 *p, u32 target) {
     }
     const u64 t0 = now_ticks();
     int spins = 0;
+    bool ok = true;
     while (true) {
         if (ld_relaxed_agent(p) >= target) break;
         __builtin_amdgcn_s_sleep(2);
         if ((++spins & 63) == 0) {
-            if (ld_relaxed_agent(&c->error) != 0) return false;
+            if (ld_relaxed_agent(&c->error) != 0) {
+                ok = false;
+                break;
+            }
             if (now_ticks() - t0 > kWaitTicks) {
                 set_error(c, MOE_ERR_TIMEOUT);
                 atomicAdd(&c->stats[6], 1ull);
-                return false;
+                ok = false;
+                break;
             }
         }
     }
-    fence_acquire(0);
-    return true;
+    atomicAdd(&c->stats[14], now_ticks() - t0);
+    if (ok) fence_acquire(0);
+    return ok;
+}
+
+// phase bookkeeping for the in-kernel timeline (ticks since the first task)
+__device__ __forceinline__ void mark_phase_end(Ctrl *c, int phase) {
+    const u64 t0 = __hip_atomic_load(&c->t0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    atomicMax(&c->stats[8 + phase], now_ticks() - t0);
 }
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((u32)b) << 16); }

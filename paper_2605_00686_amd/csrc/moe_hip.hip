@@ -66,12 +66,21 @@ __global__ __launch_bounds__(kThreads) void k_megakernel(KArgs a) {
     __shared__ int s_task, s_ok, s_last;
     Ctrl *c = a.ctrl;
     const int tid = threadIdx.x;
+    if (tid == 0) {
+        atomicCAS(&c->t0, 0ull, now_ticks());
+        atomicAdd(&c->stats[15], 1ull);
+    }
+    int phase = -1;
     while (true) {
         __syncthreads();
-        if (tid == 0) s_task = (int)atomicAdd(&c->next_task, 1u);
+        if (tid == 0) {
+            if (phase >= 0) mark_phase_end(c, phase);
+            s_task = (int)atomicAdd(&c->next_task, 1u);
+        }
         __syncthreads();
         const int task = s_task;
         if (task >= a.t_end) break;
+        phase = task < a.t_plan ? 0 : task < a.t_perm ? 1 : task < a.t_g1 ? 2 : task < a.t_g2 ? 3 : task < a.t_comb ? 4 : 5;
         if (task < a.t_plan) {
             route_task<ET>(a, task, smem, true);
             sync_stores();
@@ -133,8 +142,12 @@ __global__ __launch_bounds__(kThreads) void k_megakernel(KArgs a) {
     __syncthreads();
     if (s_last) {
         if (a.stats) {
-            if (tid < MOE_NUM_STATS - 1) a.stats[tid] = c->stats[tid];
-            if (tid == MOE_NUM_STATS - 1) a.stats[tid] = (u64)(long long)(-(int)c->error);
+            if (tid < MOE_NUM_STATS) {
+                u64 v = c->stats[tid];
+                if (tid == 7) v = (u64)(long long)(-(int)c->error);
+                if (tid >= 8 && tid <= 14) v *= 10ull;  // 100 MHz ticks -> ns
+                a.stats[tid] = v;
+            }
         }
         __syncthreads();
         u32 *z = (u32 *)c;
