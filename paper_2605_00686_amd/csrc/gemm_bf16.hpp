@@ -38,12 +38,7 @@ struct TileCfg {
     static constexpr int C_STRIDE = BN * 2 + 16;  // bytes per row of the LDS C tile (bf16, padded)
     static constexpr int C_BYTES = BM * C_STRIDE;
     static constexpr int SMEM_MAIN = (2 * STAGE > C_BYTES) ? 2 * STAGE : C_BYTES;
-    static constexpr int NA = BM / 32;   // 16-byte A pieces per thread per stage
-    static constexpr int CPR = BN / 8;   // 16-byte pieces per weight row
-    static constexpr int RPP = kThreads / CPR;  // weight rows covered per pass
-    static constexpr int NBL = BK / RPP;        // weight pieces per thread per stage
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
-    static_assert(kThreads % CPR == 0 && BK % RPP == 0, "weight tile must divide evenly");
 };
 
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
@@ -63,35 +58,38 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
     const int wm = wave / C::WN, wn = wave % C::WN;
     constexpr int HALF = C::BN / 2;
 
-    // ---- global -> register -> LDS staging assignments
-    const int a_chunk = tid & 7;  // 16-byte piece within the 128-byte K slice of a row
-    const bf16_t *a_ptr[C::NA];
-    int a_lds[C::NA];
+    // ---- global -> LDS staging.  Loads go straight into LDS (no staging
+    // registers): one instruction moves 64 lanes x 16 bytes into 1 KB of
+    // consecutive LDS, lane l landing at byte 16*l, so the XOR swizzle is
+    // applied by choosing WHICH global piece each lane fetches.
+    // A: 1 KB = 8 rows x 128 bytes; wavefront w issues rows [w*8*NA8 ...), NA8 = BM/32 per stage.
+    // B: 1 KB = 2 weight rows x 512 bytes (BN = 256).
+    static_assert(C::BN == 256, "weight tile rows are 512 bytes");
+    constexpr int NAI = C::BM / 32;  // A instructions per wavefront per stage
+    constexpr int NBI = C::BK / 8;   // B instructions per wavefront per stage (64 rows / 2 rows / 4 waves)
+    const int uw = __builtin_amdgcn_readfirstlane(wave);
+    const bf16_t *a_ptr[NAI];
 #pragma unroll
-    for (int i = 0; i < C::NA; ++i) {
-        const int row = (tid >> 3) + 32 * i;
-        a_ptr[i] = rowptr(row) + a_chunk * 8;
-        a_lds[i] = row * 128 + ((a_chunk ^ ((row >> 1) & 7)) << 4);
+    for (int i = 0; i < NAI; ++i) {
+        const int row = (uw * NAI + i) * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+        a_ptr[i] = rowptr(row) + chunk * 8;
     }
-    const int b_chunk = tid % C::CPR;
-    const int b_row0 = tid / C::CPR;
-    const bf16_t *b_ptr;
-    {
-        int col = b_chunk * 8;
+    // weight rows of instruction i: kr = (uw*NBI + i)*2 + (lane >> 5); kr & 3 depends on i's parity only
+    const bf16_t *b_ptr[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+        const int kr = par * 2 + (lane >> 5);
+        const int pc = lane & 31;
+        const int chunk = ((((pc >> 2) ^ (kr & 3)) << 2) | (pc & 3));
+        int col = chunk * 8;
         const bf16_t *base = B0;
         if (GATED && col >= HALF) {
             base = B1;
             col -= HALF;
         }
         if (col >= ncols) col = 0;  // out-of-range columns: read something valid, never stored
-        b_ptr = base + col;
-    }
-    int b_lds[C::NBL];
-#pragma unroll
-    for (int i = 0; i < C::NBL; ++i) {
-        const int kr = b_row0 + C::RPP * i;
-        const int phys = ((((b_chunk >> 2) ^ (kr & 3)) << 2) | (b_chunk & 3));
-        b_lds[i] = kr * (C::BN * 2) + (phys << 4);
+        b_ptr[par] = base + col + (size_t)(lane >> 5) * ldb;
     }
 
     // ---- fragment read addresses
@@ -121,22 +119,21 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
 
-    uint4 ra[C::NA], rb[C::NBL];
-    auto gload = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < C::NA; ++i) ra[i] = *(const uint4 *)(a_ptr[i] + kt * C::BK);
-#pragma unroll
-        for (int i = 0; i < C::NBL; ++i)
-            rb[i] = *(const uint4 *)(b_ptr + (size_t)(kt * C::BK + b_row0 + C::RPP * i) * ldb);
-    };
-    auto lstore = [&](int buf) {
+    typedef __attribute__((address_space(3))) void lds_void_t;
+    auto issue_loads = [&](int kt, int buf) {
         char *sa = smem + buf * C::STAGE;
         char *sb = sa + C::A_BYTES;
 #pragma unroll
-        for (int i = 0; i < C::NA; ++i) *(uint4 *)(sa + a_lds[i]) = ra[i];
+        for (int i = 0; i < NAI; ++i)
+            __builtin_amdgcn_global_load_lds(a_ptr[i] + kt * C::BK, (lds_void_t *)(sa + (uw * NAI + i) * 1024), 16, 0, 0);
 #pragma unroll
-        for (int i = 0; i < C::NBL; ++i) *(uint4 *)(sb + b_lds[i]) = rb[i];
+        for (int i = 0; i < NBI; ++i) {
+            const int r2 = (uw * NBI + i) * 2;  // first of the two weight rows of this instruction
+            __builtin_amdgcn_global_load_lds(b_ptr[i & 1] + (size_t)(kt * C::BK + r2) * ldb,
+                                             (lds_void_t *)(sb + r2 * (C::BN * 2)), 16, 0, 0);
+        }
     };
+    auto wait_loads = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
     auto compute = [&](int buf) {
         const char *sa = smem + buf * C::STAGE;
         const char *sb = sa + C::A_BYTES;
@@ -167,15 +164,17 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
     };
 
     const int nk = K / C::BK;
-    gload(0);
-    lstore(0);
+    issue_loads(0, 0);
+    wait_loads();
     __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) gload(kt + 1);
+    for (int kt = 0; kt < nk - 1; ++kt) {
+        issue_loads(kt + 1, (kt + 1) & 1);  // in flight while this stage is consumed
         compute(kt & 1);
-        if (kt + 1 < nk) lstore((kt + 1) & 1);
+        wait_loads();
         __syncthreads();
     }
+    compute((nk - 1) & 1);
+    __syncthreads();
 
     // ---- epilogue: fp32 accumulators -> bf16 C tile in LDS.  Lane l holds, for
     // MFMA block (mb, nb) and register group vq, output row (l & 31) and the 4
