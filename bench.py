@@ -75,6 +75,9 @@ def main():
     ap.add_argument("--scope", default="agent", choices=["agent", "system"])
     ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens for the CPU baseline (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (known HBM traffic) so that hardware byte "
+                         "counters collected around this command can be scaled")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -121,6 +124,11 @@ def main():
         print(f"bench.py: device status {stats[7]} ({B.status_string(stats[7])})", file=sys.stderr)
         sys.exit(1)
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
     ms_per_step = wall * 1e3 / args.steps
     abytes = algorithmic_bytes(cfg)
     flops = layer_flops(cfg)

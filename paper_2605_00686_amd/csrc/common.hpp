@@ -83,6 +83,7 @@ struct KArgs {
     u32 *h_ready;              // [maxRB] GEMM1 tiles finished per row block
     void *h;                   // [N][f]
     size_t zero_bytes;         // bytes from ctrl that must be zero between calls
+    int tab_lds_off;           // megakernel: LDS offset of the cached decode tables, 0 = none
 };
 
 __device__ __forceinline__ u64 now_ticks() { return wall_clock64(); }

@@ -7,31 +7,55 @@
 
 namespace moe {
 
+// LDS the plan needs, and whether its two tables are staged in LDS (they are
+// unless the problem is unusually large; then the slow global-memory path runs).
+constexpr size_t kPlanSegLds = 32 * 1024, kPlanHistLds = 32 * 1024;
+__host__ __device__ inline bool plan_seg_in_lds(int E, int R) { return (size_t)2 * E * R * 4 <= kPlanSegLds; }
+__host__ __device__ inline bool plan_hist_in_lds(int nPB, int E) { return (size_t)nPB * E * 4 <= kPlanHistLds; }
+__host__ __device__ inline size_t plan_smem_bytes(int E, int R, int nPB) {
+    size_t n = (size_t)(3 * E + R + 8) * 4;
+    if (plan_seg_in_lds(E, R)) n += (size_t)2 * E * R * 4;
+    if (plan_hist_in_lds(nPB, E)) n += (size_t)nPB * E * 4;
+    return n;
+}
+
 // Single-workgroup task.  Reads blk_hist[nPB][E] and seg_cnt[E][R] (complete),
 // writes counts, offsets, blk_base, seg_begin, flag_base, dest_flag_begin,
-// rb_base, rb_expert, ctrl->n_rb, ctrl->n_flags.
+// rb_base, rb_expert, ctrl->n_rb, ctrl->n_flags.  The inputs are first copied
+// to LDS with coalesced loads so that the serial scans below never wait on a
+// global load.
 __device__ void plan_task(const KArgs &a, char *smem) {
     const int tid = threadIdx.x;
-    const int E = a.E, R = a.R;
-    int32_t *s_cnt = (int32_t *)smem;  // [E] counts, then reused
+    const int E = a.E, R = a.R, nPB = a.nPB;
+    int32_t *s_cnt = (int32_t *)smem;  // [E]
     int32_t *s_off = s_cnt + E;        // [E+1]
     int32_t *s_dest = s_off + E + 1;   // [R+1] flags per destination, then their scan
     int32_t *s_rb = s_dest + R + 1;    // [E+1]
-
-    // per-expert totals and per-block running bases (expert-local)
+    int32_t *s_free = s_rb + E + 2;
+    const bool seg_lds = plan_seg_in_lds(E, R), hist_lds = plan_hist_in_lds(nPB, E);
+    int32_t *segc = a.seg_cnt, *segb = a.seg_begin, *hist = a.blk_base;
+    if (seg_lds) {
+        segc = s_free;
+        segb = segc + E * R;
+        s_free = segb + E * R;
+        for (int q = tid; q < E * R; q += kThreads) segc[q] = a.seg_cnt[q];
+    }
+    if (hist_lds) {
+        hist = s_free;
+        for (int q = tid; q < nPB * E; q += kThreads) hist[q] = a.blk_hist[q];
+    } else {
+        for (int q = tid; q < nPB * E; q += kThreads) hist[q] = a.blk_hist[q];  // blk_base <- blk_hist
+    }
+    __syncthreads();
+    // per expert: rows per destination -> first row of each (e, r) segment and the total
     for (int e = tid; e < E; e += kThreads) {
-        int run = 0;
-        for (int b = 0; b < a.nPB; ++b) {
-            int c = a.blk_hist[(size_t)b * E + e];
-            a.blk_base[(size_t)b * E + e] = run;
-            run += c;
-        }
-        s_cnt[e] = run;
         int sb = 0;
         for (int r = 0; r < R; ++r) {
-            a.seg_begin[(size_t)e * R + r] = sb;
-            sb += a.seg_cnt[(size_t)e * R + r];
+            const int c = segc[e * R + r];
+            segb[e * R + r] = sb;
+            sb += c;
         }
+        s_cnt[e] = sb;
     }
     __syncthreads();
     if (tid == 0) {
@@ -55,15 +79,23 @@ __device__ void plan_task(const KArgs &a, char *smem) {
             for (int i = s_rb[e]; i < s_rb[e + 1]; ++i) a.rb_expert[i] = e;
         }
     }
-    for (int q = tid; q < a.nPB * E; q += kThreads) a.blk_base[q] += s_off[q % E];
+    // sorted position of each block's first slot of e: exclusive scan over blocks
+    for (int e = tid; e < E; e += kThreads) {
+        int run = s_off[e];
+        for (int b = 0; b < nPB; ++b) {
+            const int c = hist[b * E + e];
+            hist[b * E + e] = run;
+            run += c;
+        }
+    }
     // flags: destination-major, then expert; a segment with expert-local rows
     // [b0, b0+c) touches row blocks b0/tile_m .. (b0+c-1)/tile_m
     for (int r = tid; r < R; r += kThreads) {
         int n = 0;
         for (int e = 0; e < E; ++e) {
-            int c = a.seg_cnt[(size_t)e * R + r];
+            const int c = segc[e * R + r];
             if (c > 0) {
-                int b0 = a.seg_begin[(size_t)e * R + r];
+                const int b0 = segb[e * R + r];
                 n += ((b0 + c - 1) / a.tile_m - b0 / a.tile_m + 1) * a.ncb;
             }
         }
@@ -73,7 +105,7 @@ __device__ void plan_task(const KArgs &a, char *smem) {
     if (tid == 0) {
         int run = 0;
         for (int r = 0; r < R; ++r) {
-            int n = s_dest[r];
+            const int n = s_dest[r];
             s_dest[r] = run;
             run += n;
         }
@@ -81,15 +113,19 @@ __device__ void plan_task(const KArgs &a, char *smem) {
         a.ctrl->n_flags = (u32)run;
     }
     __syncthreads();
+    if (hist_lds)
+        for (int q = tid; q < nPB * E; q += kThreads) a.blk_base[q] = hist[q];
+    if (seg_lds)
+        for (int q = tid; q < E * R; q += kThreads) a.seg_begin[q] = segb[q];
     for (int r = tid; r <= R; r += kThreads) {
         a.dest_flag_begin[r] = s_dest[r];
         if (r < R) {
             int run = s_dest[r];
             for (int e = 0; e < E; ++e) {
                 a.flag_base[(size_t)r * E + e] = run;
-                int c = a.seg_cnt[(size_t)e * R + r];
+                const int c = segc[e * R + r];
                 if (c > 0) {
-                    int b0 = a.seg_begin[(size_t)e * R + r];
+                    const int b0 = segb[e * R + r];
                     run += ((b0 + c - 1) / a.tile_m - b0 / a.tile_m + 1) * a.ncb;
                 }
             }

@@ -15,6 +15,7 @@ struct Bf16Policy {
     static constexpr int BM = C::BM, BN1 = C::BN / 2, BN2 = C::BN;
     static constexpr int C_STRIDE = C::C_STRIDE;
     static constexpr int SMEM_MAIN = C::SMEM_MAIN;
+    static constexpr int MIN_WAVES = (C::BM <= 32) ? 2 : 1;  // wavefronts per SIMD the kernel is built for
     template <bool GATED, class RowPtr>
     static __device__ __forceinline__ void gemm(RowPtr rp, const ET *B0, const ET *B1, int ldb, int ncols, int K,
                                                 char *smem) {
@@ -26,6 +27,7 @@ struct F32Policy {
     static constexpr int BM = TileF32::BM, BN1 = TileF32::BN, BN2 = TileF32::BN;
     static constexpr int C_STRIDE = TileF32::C_STRIDE;
     static constexpr int SMEM_MAIN = TileF32::SMEM_MAIN;
+    static constexpr int MIN_WAVES = 1;
     template <bool GATED, class RowPtr>
     static __device__ __forceinline__ void gemm(RowPtr rp, const ET *B0, const ET *B1, int ldb, int ncols, int K,
                                                 char *smem) {
@@ -47,25 +49,33 @@ struct TileInfo {
     bool valid;
 };
 
+// The three small tables a tile decode reads; they point into LDS once a
+// workgroup has copied them there (after the plan), else into the workspace.
+struct Tables {
+    const int32_t *offsets, *rb_base, *rb_expert;
+    int n_rb;
+};
+
 // Task -> tile.  Tiles of one expert are consecutive; inside an expert the
 // column tile varies slowest, so tiles running at the same time share one
 // weight column block and the expert's rows (the re-read operand is the small
 // one and stays in cache).
-__device__ __forceinline__ TileInfo decode_tile(const KArgs &a, int lt, int NT, int BN, int total_cols) {
+__device__ __forceinline__ TileInfo decode_tile(const KArgs &a, const Tables &tb, int lt, int NT, int BN,
+                                                int total_cols) {
     TileInfo ti;
     ti.valid = false;
     const int vrb = lt / NT;
-    if (vrb >= (int)a.ctrl->n_rb) return ti;
-    const int e = a.rb_expert[vrb];
-    const int base = a.rb_base[e];
-    const int nrb = a.rb_base[e + 1] - base;
+    if (vrb >= tb.n_rb) return ti;
+    const int e = tb.rb_expert[vrb];
+    const int base = tb.rb_base[e];
+    const int nrb = tb.rb_base[e + 1] - base;
     const int loc = lt - base * NT;
     const int ct = loc / nrb, rbl = loc % nrb;
     ti.e = e;
     ti.rb = base + rbl;
     ti.lrow0 = rbl * a.tl.BM;
-    ti.row0 = a.offsets[e] + ti.lrow0;
-    ti.nrows = min(a.tl.BM, a.offsets[e + 1] - ti.row0);
+    ti.row0 = tb.offsets[e] + ti.lrow0;
+    ti.nrows = min(a.tl.BM, tb.offsets[e + 1] - ti.row0);
     ti.n0 = ct * BN;
     ti.ncols = min(BN, total_cols - ti.n0);
     ti.valid = true;
@@ -76,9 +86,9 @@ __device__ __forceinline__ TileInfo decode_tile(const KArgs &a, int lt, int NT, 
 // Rows are gathered straight from x through perm: the permuted activations are
 // never materialised.
 template <class P>
-__device__ void g1_tile(const KArgs &a, int lt, char *smem) {
+__device__ void g1_tile(const KArgs &a, const Tables &tb, int lt, char *smem) {
     using ET = typename P::ET;
-    const TileInfo ti = decode_tile(a, lt, a.tl.NT1, P::BN1, a.f);
+    const TileInfo ti = decode_tile(a, tb, lt, a.tl.NT1, P::BN1, a.f);
     if (!ti.valid) return;
     const ET *x = (const ET *)a.x;
     const int N = a.N;
@@ -278,81 +288,98 @@ struct Vec16<float> {
 };
 
 // out[t] = sum_j w[t,j] * staging[t*k+j] for the tokens of one task.  WAIT:
-// spin (bounded) until the flags covering the token's rows carry this call's
+// spin (bounded) until the flags covering the task's rows carry this call's
 // epoch; otherwise check once and report.  Flags are read with relaxed atomic
-// loads followed by one acquire fence at the requested scope.
+// loads (a first pass that keeps many loads in flight, then a spin on whatever
+// was not ready) followed by one acquire fence at the requested scope.  Then
+// one wavefront per token, 16-byte pieces, up to eight rows in flight per lane.
 template <typename ET, bool WAIT>
 __device__ void combine_task(const KArgs &a, int task) {
     using V = Vec16<ET>;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int k = a.k, sys = a.fence_scope;
     const char *staging = (const char *)a.staging;
     const int pieces = a.d * (int)sizeof(ET) / 16;
-    for (int tt = 0; tt < a.comb_tokens; ++tt) {
-        const int t = task * a.comb_tokens + tt;
-        if (t >= a.T) break;
-        if (a.slot_flag && a.flags) {
-            bool ok = true;
-            for (int q = tid; q < k * a.ncb; q += kThreads) {
-                const u32 *fp = &a.flags[a.slot_flag[(size_t)t * k + q / a.ncb] + q % a.ncb];
-                if (WAIT) {
-                    const u64 t0 = now_ticks();
-                    int spins = 0;
-                    while (ld_relaxed(fp, sys) != a.epoch) {
-                        __builtin_amdgcn_s_sleep(2);
-                        if ((++spins & 63) == 0) {
-                            if (ld_relaxed_agent(&a.ctrl->error) != 0) break;
-                            if (now_ticks() - t0 > kWaitTicks) {
-                                set_error(a.ctrl, MOE_ERR_TIMEOUT);
-                                atomicAdd(&a.ctrl->stats[6], 1ull);
-                                break;
-                            }
+    const int t_first = task * a.comb_tokens;
+    const int nt = min(a.comb_tokens, a.T - t_first);
+    if (a.slot_flag && a.flags) {
+        const int per_tok = k * a.ncb;
+        const int nflag = nt * per_tok;
+        bool ok = true;
+#pragma unroll 4
+        for (int q = tid; q < nflag; q += kThreads) {
+            const int slot = t_first * k + q / a.ncb;
+            ok = ok && (ld_relaxed(&a.flags[a.slot_flag[slot] + q % a.ncb], sys) == a.epoch);
+        }
+        if (WAIT && !ok) {
+            for (int q = tid; q < nflag; q += kThreads) {
+                const int slot = t_first * k + q / a.ncb;
+                const u32 *fp = &a.flags[a.slot_flag[slot] + q % a.ncb];
+                const u64 t0 = now_ticks();
+                int spins = 0;
+                while (ld_relaxed(fp, sys) != a.epoch) {
+                    __builtin_amdgcn_s_sleep(2);
+                    if ((++spins & 63) == 0) {
+                        if (ld_relaxed_agent(&a.ctrl->error) != 0) break;
+                        if (now_ticks() - t0 > kWaitTicks) {
+                            set_error(a.ctrl, MOE_ERR_TIMEOUT);
+                            atomicAdd(&a.ctrl->stats[6], 1ull);
+                            break;
                         }
                     }
-                } else {
-                    ok = ok && (ld_relaxed(fp, sys) == a.epoch);
                 }
+                atomicAdd(&a.ctrl->stats[14], now_ticks() - t0);
             }
-            fence_acquire(sys);
-            if (!WAIT && !ok && a.status_dev) atomicExch(a.status_dev, (int)MOE_ERR_NOT_READY);
         }
-        __syncthreads();
-        for (int c = tid; c < pieces; c += kThreads) {
+        fence_acquire(sys);
+        if (!WAIT && !ok && a.status_dev) atomicExch(a.status_dev, (int)MOE_ERR_NOT_READY);
+        __syncthreads();  // rows guarded by flags another lane polled
+    }
+    const size_t rstride = (size_t)a.d * sizeof(ET);
+    for (int tt = wave; tt < nt; tt += 4) {
+        const int t = t_first + tt;
+        const float *wt = a.w + (size_t)t * k;
+        for (int c = lane; c < pieces; c += 64) {
             float acc[V::N];
 #pragma unroll
             for (int i = 0; i < V::N; ++i) acc[i] = 0.f;
-            const char *row = staging + ((size_t)t * k * a.d) * sizeof(ET) + (size_t)c * 16;
-            const size_t rstride = (size_t)a.d * sizeof(ET);
+            const char *row = staging + (size_t)t * k * rstride + (size_t)c * 16;
             int j = 0;
-            for (; j + 4 <= k; j += 4) {
+            for (; j + 8 <= k; j += 8) {
+                uint4 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = *(const uint4 *)(row + (size_t)(j + u) * rstride);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    float f[V::N];
+                    V::unpack(v[u], f);
+                    const float wj = wt[j + u];
+#pragma unroll
+                    for (int i = 0; i < V::N; ++i) acc[i] = fmaf(wj, f[i], acc[i]);
+                }
+            }
+            for (; j + 2 <= k; j += 2) {
                 const uint4 v0 = *(const uint4 *)(row + (size_t)j * rstride);
                 const uint4 v1 = *(const uint4 *)(row + (size_t)(j + 1) * rstride);
-                const uint4 v2 = *(const uint4 *)(row + (size_t)(j + 2) * rstride);
-                const uint4 v3 = *(const uint4 *)(row + (size_t)(j + 3) * rstride);
-                float f0[V::N], f1[V::N], f2[V::N], f3[V::N];
+                float f0[V::N], f1[V::N];
                 V::unpack(v0, f0);
                 V::unpack(v1, f1);
-                V::unpack(v2, f2);
-                V::unpack(v3, f3);
-                const float w0 = a.w[(size_t)t * k + j], w1 = a.w[(size_t)t * k + j + 1];
-                const float w2 = a.w[(size_t)t * k + j + 2], w3 = a.w[(size_t)t * k + j + 3];
+                const float w0 = wt[j], w1 = wt[j + 1];
 #pragma unroll
                 for (int i = 0; i < V::N; ++i) {
                     acc[i] = fmaf(w0, f0[i], acc[i]);
                     acc[i] = fmaf(w1, f1[i], acc[i]);
-                    acc[i] = fmaf(w2, f2[i], acc[i]);
-                    acc[i] = fmaf(w3, f3[i], acc[i]);
                 }
             }
             for (; j < k; ++j) {
                 const uint4 v0 = *(const uint4 *)(row + (size_t)j * rstride);
                 float f0[V::N];
                 V::unpack(v0, f0);
-                const float w0 = a.w[(size_t)t * k + j];
+                const float w0 = wt[j];
 #pragma unroll
                 for (int i = 0; i < V::N; ++i) acc[i] = fmaf(w0, f0[i], acc[i]);
             }
-            V::store((char *)a.out + ((size_t)t * a.d) * sizeof(ET) + (size_t)c * 16, acc);
+            V::store((char *)a.out + (size_t)t * rstride + (size_t)c * 16, acc);
         }
     }
 }

@@ -57,10 +57,13 @@ __global__ __launch_bounds__(kThreads) void k_combine(KArgs a) {
 // The whole layer in one persistent kernel.  Workgroups draw task numbers from
 // one counter; the task list is ordered so that a task only ever waits for
 // lower-numbered tasks, all of which have been drawn by workgroups that are
-// already running: no wait can deadlock, whatever the grid size.
+// already running: no wait can deadlock, whatever the grid size.  (A workgroup
+// draws its next task while it works on the current one, which hides the
+// counter's latency and keeps the argument intact: the task in hand only waits
+// for lower-numbered ones.)
 //   [gate tasks | plan | permutation blocks | GEMM1 tiles | GEMM2 tiles | combine tasks]
 template <class P>
-__global__ __launch_bounds__(kThreads) void k_megakernel(KArgs a) {
+__global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) {
     using ET = typename P::ET;
     extern __shared__ __align__(16) char smem[];
     __shared__ int s_task, s_ok, s_last;
@@ -69,19 +72,59 @@ __global__ __launch_bounds__(kThreads) void k_megakernel(KArgs a) {
     if (tid == 0) {
         atomicCAS(&c->t0, 0ull, now_ticks());
         atomicAdd(&c->stats[15], 1ull);
+        s_task = (int)atomicAdd(&c->next_task, 1u);
     }
-    int phase = -1;
-    while (true) {
+    __syncthreads();
+    int task = s_task;
+    // what this workgroup has already observed (uniform across its threads)
+    bool seen_plan = false, seen_perm = false, bad = false;
+    Tables tb;
+    tb.offsets = a.offsets;
+    tb.rb_base = a.rb_base;
+    tb.rb_expert = a.rb_expert;
+    tb.n_rb = 0;
+
+    // wait once for the plan (and with it for every gate task); copy the decode tables to LDS
+    auto need_plan = [&]() {
+        if (seen_plan) return;
+        if (tid == 0) s_ok = (wait_ge(c, &c->plan_done, 1u) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
         __syncthreads();
-        if (tid == 0) {
-            if (phase >= 0) mark_phase_end(c, phase);
-            s_task = (int)atomicAdd(&c->next_task, 1u);
+        seen_plan = true;
+        bad = bad || !s_ok;
+        if (!bad) {
+            tb.n_rb = (int)c->n_rb;
+            if (a.tab_lds_off > 0) {
+                int32_t *t_off = (int32_t *)(smem + a.tab_lds_off);
+                int32_t *t_rbb = t_off + a.E + 1;
+                int32_t *t_rbe = t_rbb + a.E + 1;
+                for (int i = tid; i <= a.E; i += kThreads) {
+                    t_off[i] = a.offsets[i];
+                    t_rbb[i] = a.rb_base[i];
+                }
+                for (int i = tid; i < tb.n_rb; i += kThreads) t_rbe[i] = a.rb_expert[i];
+                tb.offsets = t_off;
+                tb.rb_base = t_rbb;
+                tb.rb_expert = t_rbe;
+            }
         }
         __syncthreads();
-        const int task = s_task;
-        if (task >= a.t_end) break;
-        phase = task < a.t_plan ? 0 : task < a.t_perm ? 1 : task < a.t_g1 ? 2 : task < a.t_g2 ? 3 : task < a.t_comb ? 4 : 5;
+    };
+    auto need_perm = [&]() {
+        need_plan();
+        if (seen_perm) return;
+        if (tid == 0) s_ok = wait_ge(c, &c->perm_done, (u32)a.nPB) ? 1 : 0;
+        __syncthreads();
+        seen_perm = true;
+        bad = bad || !s_ok;
+        __syncthreads();
+    };
+
+    while (task < a.t_end) {
+        u32 next = 0;
+        if (tid == 0) next = atomicAdd(&c->next_task, 1u);  // consumed at the end of this task
+        int phase;
         if (task < a.t_plan) {
+            phase = 0;
             route_task<ET>(a, task, smem, true);
             sync_stores();
             if (tid == 0) {
@@ -89,6 +132,7 @@ __global__ __launch_bounds__(kThreads) void k_megakernel(KArgs a) {
                 atomicAdd(&c->route_done, 1u);
             }
         } else if (task < a.t_perm) {
+            phase = 1;
             if (tid == 0) s_ok = wait_ge(c, &c->route_done, (u32)a.nRT) ? 1 : 0;
             __syncthreads();
             if (s_ok) plan_task(a, smem);
@@ -98,38 +142,41 @@ __global__ __launch_bounds__(kThreads) void k_megakernel(KArgs a) {
                 __hip_atomic_store(&c->plan_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         } else if (task < a.t_g1) {
-            if (tid == 0) s_ok = (wait_ge(c, &c->plan_done, 1u) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
-            __syncthreads();
-            if (s_ok) perm_task<ET>(a, task - a.t_perm, smem);
+            phase = 2;
+            need_plan();
+            if (!bad) perm_task<ET>(a, task - a.t_perm, smem);
             sync_stores();
             if (tid == 0) {
                 fence_release(0);
                 atomicAdd(&c->perm_done, 1u);
             }
         } else if (task < a.t_g2) {
-            if (tid == 0) s_ok = (wait_ge(c, &c->perm_done, (u32)a.nPB) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
-            __syncthreads();
-            if (s_ok) g1_tile<P>(a, task - a.t_g1, smem);
+            phase = 3;
+            need_perm();
+            if (!bad) g1_tile<P>(a, tb, task - a.t_g1, smem);
         } else if (task < a.t_comb) {
-            // plan_done is implied: this workgroup or an earlier task already waited for it,
-            // but a workgroup may arrive here without having done so -> wait again (cheap).
-            if (tid == 0) s_ok = wait_ge(c, &c->plan_done, 1u) ? 1 : 0;
-            __syncthreads();
+            phase = 4;
+            need_plan();
             TileInfo ti;
             ti.valid = false;
-            if (s_ok) ti = decode_tile(a, task - a.t_g2, a.tl.NT2, P::BN2, a.d);
+            if (!bad) ti = decode_tile(a, tb, task - a.t_g2, a.tl.NT2, P::BN2, a.d);
             if (ti.valid) {  // uniform: every thread decodes the same tile
-                __syncthreads();
-                if (tid == 0)
-                    s_ok = (wait_ge(c, &a.h_ready[ti.rb], (u32)a.tl.NT1) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
+                if (tid == 0) s_ok = wait_ge(c, &a.h_ready[ti.rb], (u32)a.tl.NT1) ? 1 : 0;
                 __syncthreads();
                 if (s_ok) g2_tile<P>(a, ti, smem);
             }
         } else {
-            if (tid == 0) s_ok = (wait_ge(c, &c->perm_done, (u32)a.nPB) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
-            __syncthreads();
-            if (s_ok) combine_task<ET, true>(a, task - a.t_comb);
+            phase = 5;
+            need_perm();
+            if (!bad) combine_task<ET, true>(a, task - a.t_comb);
         }
+        __syncthreads();
+        if (tid == 0) {
+            mark_phase_end(c, phase);
+            s_task = (int)next;
+        }
+        __syncthreads();
+        task = s_task;
     }
     // last workgroup out copies the statistics and clears the control block
     sync_stores();
@@ -196,7 +243,7 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     pl->ncb = (p->d + tn - 1) / tn;
     pl->nPB = (p->T + kPermBlock - 1) / kPermBlock;
     pl->nRT = (p->T + kRouteTokens - 1) / kRouteTokens;
-    pl->comb_tokens = (p->T >= 8192) ? 4 : 1;
+    pl->comb_tokens = p->T >= 16384 ? 16 : p->T >= 8192 ? 8 : p->T >= 2048 ? 4 : 1;
     pl->nCT = (p->T + pl->comb_tokens - 1) / pl->comb_tokens;
     // tile shape: the smallest row block that holds an average expert, never
     // smaller than the publish tile (a publish tile must not span two compute tiles)
@@ -281,7 +328,7 @@ static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
     }
 }
 
-static size_t plan_smem(const Plan &pl) { return (size_t)(3 * pl.p.E + pl.p.R + 8) * 4; }
+static size_t plan_smem(const Plan &pl) { return plan_smem_bytes(pl.p.E, pl.p.R, pl.nPB); }
 
 static int check_ws(const void *ws) {
     if (!ws || ((uintptr_t)ws & 255u)) return MOE_ERR_WORKSPACE;
@@ -299,10 +346,18 @@ static int set_smem(K kernel, size_t bytes) {
 }
 
 template <class P>
-static int launch_mega(const Plan &pl, const KArgs &a, hipStream_t st) {
+static int launch_mega(const Plan &pl, const KArgs &a_in, hipStream_t st) {
     size_t smem = tile_smem_bytes<P>();
-    if (a.Wg && route_smem_bytes(pl.p.E) > smem) smem = route_smem_bytes(pl.p.E);
+    if (a_in.Wg && route_smem_bytes(pl.p.E) > smem) smem = route_smem_bytes(pl.p.E);
     if (plan_smem(pl) > smem) smem = plan_smem(pl);
+    // decode tables live behind everything else, for the life of the workgroup
+    KArgs a = a_in;
+    const size_t tab_bytes = (size_t)(2 * (pl.p.E + 1) + pl.tl.maxRB) * 4;
+    a.tab_lds_off = 0;
+    if (tab_bytes <= 8 * 1024) {
+        a.tab_lds_off = (int)align_up(smem, 16);
+        smem = a.tab_lds_off + tab_bytes;
+    }
     auto kern = k_megakernel<P>;
     int rc = set_smem(kern, smem);
     if (rc) return rc;

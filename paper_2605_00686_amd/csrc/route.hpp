@@ -6,18 +6,10 @@
 
 namespace moe {
 
-constexpr int kRouteKC = 64;  // reduction chunk staged in LDS
+typedef __attribute__((ext_vector_type(4))) double f64x4_t;
 
-__host__ __device__ inline int route_lanes_e(int E) {
-    int l = 1;
-    while (l < E && l < 32) l <<= 1;
-    return l;
-}
 __host__ __device__ inline size_t route_smem_bytes(int E) {
-    // x chunk [16][KC+4] f32, Wg chunk transposed [E][KC+4] f32, logits [16][E] f64
-    size_t a = (size_t)kRouteTokens * (kRouteKC + 4) * 4 + (size_t)E * (kRouteKC + 4) * 4;
-    size_t b = (size_t)kRouteTokens * E * 8;
-    return a + b;
+    return (size_t)kRouteTokens * E * 8;  // logits [16][E] f64
 }
 
 // (value, index) argmax step: larger value wins, equal values -> lower index
@@ -28,94 +20,99 @@ __device__ __forceinline__ void argmax_merge(double &v, int &i, double ov, int o
     }
 }
 
-// Logits of tokens [t0, t0+16) into lg[16][E] (LDS, fp64).  Thread (e_lane,
-// t_lane) owns experts e_lane + lanes_e*j (j < NE) and tokens t_lane + t_lanes*n
-// (n < NT); bf16/fp32 products are exact in fp64, so the only rounding is the
-// fp64 accumulation itself.
-template <typename ET, int NE, int NT>
-__device__ void route_logits(const KArgs &a, int t0, char *smem) {
-    const int tid = threadIdx.x;
+template <typename ET>
+struct RouteLoad;
+template <>
+struct RouteLoad<bf16_t> {
+    typedef uint2 x4_t;  // four consecutive bf16
+    static __device__ __forceinline__ double get(const x4_t &v, int s) {
+        const u32 w = (s < 2) ? v.x : v.y;
+        return (double)__uint_as_float((s & 1) ? (w & 0xffff0000u) : (w << 16));
+    }
+    static __device__ __forceinline__ double one(const bf16_t *p) { return (double)bf16_to_f32(*p); }
+};
+template <>
+struct RouteLoad<float> {
+    typedef float4 x4_t;
+    static __device__ __forceinline__ double get(const x4_t &v, int s) {
+        return (double)(s == 0 ? v.x : s == 1 ? v.y : s == 2 ? v.z : v.w);
+    }
+    static __device__ __forceinline__ double one(const float *p) { return (double)*p; }
+};
+
+// Logits of tokens [t0, t0+16) into lg[16][E] (LDS, fp64) with the fp64 matrix
+// cores: D[token][expert] += x[token][k] * Wg[k][expert], 16 x 16 x 4 per
+// instruction.  bf16/fp32 inputs convert exactly and their products are exact
+// in fp64, so the only rounding is the fp64 accumulation.  Lane l feeds token
+// (or expert) l % 16 and reduction index 4*(l / 16) + s within a chunk of 16;
+// the four wavefronts take contiguous quarters of the reduction and add their
+// partial sums into LDS one after the other (fixed order: deterministic).
+template <typename ET, int NB>
+__device__ void route_logits(const KArgs &a, int t0, int eb0, char *smem) {
+    typedef RouteLoad<ET> L;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int E = a.E, d = a.d;
-    const int lanes_e = route_lanes_e(E);
-    const int t_lanes = kThreads / lanes_e;
-    const int e_lane = tid % lanes_e, t_lane = tid / lanes_e;
-    constexpr int LD = kRouteKC + 4;
-    float *xs = (float *)smem;             // [16][LD]
-    float *ws = xs + kRouteTokens * LD;    // [E][LD]
-    double *lg = (double *)(ws + E * LD);  // [16][E]
+    const int li = lane & 15, kq = lane >> 4;
+    double *lg = (double *)smem;  // [16][E]
     const ET *x = (const ET *)a.x;
     const ET *Wg = (const ET *)a.Wg;
+    const int nchunk = d / 16;
+    const int c_begin = (nchunk * wave) / 4, c_end = (nchunk * (wave + 1)) / 4;
+    const int tok = min(t0 + li, a.T - 1);
+    const ET *xrow = x + (size_t)tok * d + 4 * kq;
 
-    double acc[NE][NT];
+    f64x4_t acc[NB];
 #pragma unroll
-    for (int j = 0; j < NE; ++j)
-#pragma unroll
-        for (int n = 0; n < NT; ++n) acc[j][n] = 0.0;
+    for (int eb = 0; eb < NB; ++eb) acc[eb] = f64x4_t{0.0, 0.0, 0.0, 0.0};
+    // expert column of this lane in block eb0 + eb; lanes past E feed zeros
+    const ET *wcol = Wg + (size_t)(4 * kq) * E + eb0 * 16 + li;
 
-    for (int i0 = 0; i0 < d; i0 += kRouteKC) {
-        const int kc = min(kRouteKC, d - i0);
-        for (int q = tid; q < kRouteTokens * kRouteKC; q += kThreads) {
-            int t = q / kRouteKC, i = q % kRouteKC;
-            float v = 0.f;
-            if (t0 + t < a.T && i < kc) v = Elem<ET>::load(x, (size_t)(t0 + t) * d + i0 + i);
-            xs[t * LD + i] = v;
+    for (int c = c_begin; c < c_end; ++c) {
+        const typename L::x4_t xv = *(const typename L::x4_t *)(xrow + c * 16);
+        const ET *wrow = wcol + (size_t)(c * 16) * E;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const double av = L::get(xv, s);
+            double bv[NB];
+#pragma unroll
+            for (int eb = 0; eb < NB; ++eb)
+                bv[eb] = ((eb0 + eb) * 16 + li < E) ? L::one(wrow + (size_t)s * E + eb * 16) : 0.0;
+#pragma unroll
+            for (int eb = 0; eb < NB; ++eb)
+                acc[eb] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv[eb], acc[eb], 0, 0, 0);
         }
-        for (int q = tid; q < kRouteKC * E; q += kThreads) {
-            int i = q / E, e = q % E;  // consecutive threads -> consecutive e: coalesced
-            float v = 0.f;
-            if (i < kc) v = Elem<ET>::load(Wg, (size_t)(i0 + i) * E + e);
-            ws[e * LD + i] = v;
-        }
-        __syncthreads();
-#pragma unroll 2
-        for (int i = 0; i < kRouteKC; i += 4) {
-            float4 xv[NT], wv[NE];
+    }
+    // D layout: lane l, register v -> token 4*v + l/16, expert (block) l % 16
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
 #pragma unroll
-            for (int n = 0; n < NT; ++n) {
-                int t = t_lane + t_lanes * n;
-                xv[n] = (t < kRouteTokens) ? *(const float4 *)&xs[t * LD + i] : make_float4(0, 0, 0, 0);
-            }
+            for (int eb = 0; eb < NB; ++eb) {
+                const int e = (eb0 + eb) * 16 + li;
+                if (e < E) {
 #pragma unroll
-            for (int j = 0; j < NE; ++j) {
-                int e = e_lane + lanes_e * j;
-                wv[j] = (e < E) ? *(const float4 *)&ws[e * LD + i] : make_float4(0, 0, 0, 0);
-            }
-#pragma unroll
-            for (int j = 0; j < NE; ++j)
-#pragma unroll
-                for (int n = 0; n < NT; ++n) {
-                    acc[j][n] = fma((double)xv[n].x, (double)wv[j].x, acc[j][n]);
-                    acc[j][n] = fma((double)xv[n].y, (double)wv[j].y, acc[j][n]);
-                    acc[j][n] = fma((double)xv[n].z, (double)wv[j].z, acc[j][n]);
-                    acc[j][n] = fma((double)xv[n].w, (double)wv[j].w, acc[j][n]);
+                    for (int v = 0; v < 4; ++v) {
+                        const int t = 4 * v + kq;
+                        const double prev = (w == 0) ? (a.bias ? (double)a.bias[e] : 0.0) : lg[t * E + e];
+                        lg[t * E + e] = prev + acc[eb][v];
+                    }
                 }
+            }
         }
         __syncthreads();
     }
-#pragma unroll
-    for (int j = 0; j < NE; ++j)
-#pragma unroll
-        for (int n = 0; n < NT; ++n) {
-            int e = e_lane + lanes_e * j, t = t_lane + t_lanes * n;
-            if (e < E && t < kRouteTokens) lg[t * E + e] = acc[j][n] + (a.bias ? (double)a.bias[e] : 0.0);
-        }
-    __syncthreads();
 }
 
 template <typename ET>
 __device__ void route_logits_dispatch(const KArgs &a, int t0, char *smem) {
-    const int lanes_e = route_lanes_e(a.E);
-    const int ne = (a.E + lanes_e - 1) / lanes_e;
-    if (lanes_e < 32)
-        route_logits<ET, 1, 1>(a, t0, smem);
-    else if (ne <= 1)
-        route_logits<ET, 1, 2>(a, t0, smem);
-    else if (ne <= 2)
-        route_logits<ET, 2, 2>(a, t0, smem);
-    else if (ne <= 4)
-        route_logits<ET, 4, 2>(a, t0, smem);
+    const int nb = (a.E + 15) / 16;
+    if (nb <= 1)
+        route_logits<ET, 1>(a, t0, 0, smem);
+    else if (nb <= 2)
+        route_logits<ET, 2>(a, t0, 0, smem);
+    else if (nb <= 4)
+        route_logits<ET, 4>(a, t0, 0, smem);
     else
-        route_logits<ET, 8, 2>(a, t0, smem);
+        for (int eb0 = 0; eb0 < nb; eb0 += 8) route_logits<ET, 8>(a, t0, eb0, smem);  // 128 experts per pass
 }
 
 // One gate task: tokens [task*16, task*16+16).  With a.Wg == NULL the routing
@@ -127,7 +124,7 @@ __device__ void route_task(const KArgs &a, int task, char *smem, bool do_hist) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool compute = (a.Wg != nullptr);
     if (compute) route_logits_dispatch<ET>(a, t0, smem);
-    const double *lg = (const double *)((float *)smem + (kRouteTokens + E) * (kRouteKC + 4));
+    const double *lg = (const double *)smem;
     const double NEG = -__builtin_huge_val();
 
     for (int tl = wave; tl < kRouteTokens; tl += 4) {
