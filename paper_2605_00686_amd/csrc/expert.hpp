@@ -40,9 +40,10 @@ constexpr int tile_smem_bytes() {
     return P::SMEM_MAIN + (3 * P::BM + 8) * 4;
 }
 
-using CfgL = TileCfg<4, 4, 2, 2>;  // 256 x 256, wavefront 128 x 128
-using CfgM = TileCfg<2, 4, 2, 2>;  // 128 x 256, wavefront  64 x 128
-using CfgS = TileCfg<1, 2, 1, 4>;  //  32 x 256, wavefront  32 x  64
+// stage depth / count per shape: the best of the variants measured on MI355X
+using CfgL = TileCfg<4, 4, 2, 2, 64, 2>;  // 256 x 256, wavefront 128 x 128
+using CfgM = TileCfg<2, 4, 2, 2, 64, 3>;  // 128 x 256, wavefront  64 x 128
+using CfgS = TileCfg<1, 2, 1, 4, 64, 2>;  //  32 x 256, wavefront  32 x  64, two workgroups per CU
 
 struct TileInfo {
     int e, rb, row0, nrows, lrow0, n0, ncols;

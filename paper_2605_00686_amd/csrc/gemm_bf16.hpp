@@ -12,8 +12,13 @@
 //  * The product is formed transposed (weights as the first MFMA operand), so
 //    a lane ends up with 4 consecutive output columns of one output row and
 //    can write them as one 8-byte piece.
-//  * LDS tiles are XOR-swizzled so that both the 16-byte writes and the
-//    fragment reads are bank-conflict free.
+//  * Global loads go straight into LDS (no staging registers): one instruction
+//    moves 64 lanes x 16 bytes into 1 KB of consecutive LDS, lane l landing at
+//    byte 16*l.  LDS tiles are XOR-swizzled so that fragment reads are free of
+//    bank conflicts; since the destination of a direct load is fixed, the
+//    swizzle is applied by choosing WHICH global piece each lane fetches.
+//  * NS pipeline stages of BK reduction steps each: loads run NS-1 stages ahead
+//    of the MFMAs, one workgroup barrier per stage.
 #pragma once
 #include "common.hpp"
 
@@ -24,24 +29,38 @@ typedef __attribute__((ext_vector_type(8))) short s16x8_t;
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
-// MB x NB MFMA blocks (32 x 32) per wavefront, WM x WN wavefronts (WM*WN = 4).
-template <int MB_, int NB_, int WM_, int WN_>
+// MB x NB MFMA blocks (32 x 32) per wavefront, WM x WN wavefronts (WM*WN = 4),
+// BK reduction steps per stage (32 or 64), NS stages.
+template <int MB_, int NB_, int WM_, int WN_, int BK_, int NS_>
 struct TileCfg {
-    static constexpr int MB = MB_, NB = NB_, WM = WM_, WN = WN_;
+    static constexpr int MB = MB_, NB = NB_, WM = WM_, WN = WN_, BK = BK_, NS = NS_;
     static constexpr int BM = 32 * MB * WM;   // rows per tile
     static constexpr int BNW = 32 * NB;       // weight columns per wavefront
     static constexpr int BN = BNW * WN;       // weight columns per tile (gated: half from W1, half from W3)
-    static constexpr int BK = 64;             // K per pipeline stage
-    static constexpr int A_BYTES = BM * BK * 2;
+    static constexpr int A_ROW = BK * 2;      // bytes of one A row in a stage
+    static constexpr int A_BYTES = BM * A_ROW;
     static constexpr int B_BYTES = BK * BN * 2;
     static constexpr int STAGE = A_BYTES + B_BYTES;
     static constexpr int C_STRIDE = BN * 2 + 16;  // bytes per row of the LDS C tile (bf16, padded)
     static constexpr int C_BYTES = BM * C_STRIDE;
-    static constexpr int SMEM_MAIN = (2 * STAGE > C_BYTES) ? 2 * STAGE : C_BYTES;
+    static constexpr int SMEM_MAIN = (NS * STAGE > C_BYTES) ? NS * STAGE : C_BYTES;
+    // direct loads: 1 KB each; every wavefront issues the same number per stage
+    static constexpr int A_INSTR = A_BYTES / 1024;
+    static constexpr int NAI = (A_INSTR + 3) / 4;   // A loads per wavefront per stage
+    static constexpr int NBI = B_BYTES / 1024 / 4;  // B loads per wavefront per stage
+    static constexpr int LPS = NAI + NBI;           // loads per wavefront per stage
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
+    static_assert(BN == 256, "weight tile rows are 512 bytes");
+    static_assert(BK == 32 || BK == 64, "stage depth");
+    static_assert((NS - 2) * LPS <= 63, "vmcnt range");
 };
 
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 // Main loop + epilogue into LDS.
 //   rowptr(r): pointer to local row r of A (K contiguous bf16), valid for every r < BM
@@ -57,25 +76,27 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / C::WN, wn = wave % C::WN;
     constexpr int HALF = C::BN / 2;
+    constexpr int CPRA = C::BK / 8;            // 16-byte pieces per A row
+    constexpr int RPI = 1024 / C::A_ROW;       // A rows per load instruction
+    // swizzle of the A tile: piece c of row r sits at piece c ^ swz(r)
+    auto a_swz = [](int row) { return C::BK == 64 ? ((row >> 1) & 7) : ((row >> 2) & 3); };
 
-    // ---- global -> LDS staging.  Loads go straight into LDS (no staging
-    // registers): one instruction moves 64 lanes x 16 bytes into 1 KB of
-    // consecutive LDS, lane l landing at byte 16*l, so the XOR swizzle is
-    // applied by choosing WHICH global piece each lane fetches.
-    // A: 1 KB = 8 rows x 128 bytes; wavefront w issues rows [w*8*NA8 ...), NA8 = BM/32 per stage.
-    // B: 1 KB = 2 weight rows x 512 bytes (BN = 256).
-    static_assert(C::BN == 256, "weight tile rows are 512 bytes");
-    constexpr int NAI = C::BM / 32;  // A instructions per wavefront per stage
-    constexpr int NBI = C::BK / 8;   // B instructions per wavefront per stage (64 rows / 2 rows / 4 waves)
     const int uw = __builtin_amdgcn_readfirstlane(wave);
-    const bf16_t *a_ptr[NAI];
+    // ---- A loads.  Instruction (uw*NAI + i) covers rows [.. * RPI, +RPI); when the
+    // tile has fewer than 4 instructions the upper wavefronts repeat the lower ones'
+    // loads (same bytes to the same place) so that all wavefronts count alike.
+    const bf16_t *a_ptr[C::NAI];
+    int a_dst[C::NAI];
 #pragma unroll
-    for (int i = 0; i < NAI; ++i) {
-        const int row = (uw * NAI + i) * 8 + (lane >> 3);
-        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+    for (int i = 0; i < C::NAI; ++i) {
+        const int instr = (uw * C::NAI + i) % C::A_INSTR;
+        const int row = instr * RPI + lane / CPRA;
+        const int chunk = (lane % CPRA) ^ a_swz(row);
         a_ptr[i] = rowptr(row) + chunk * 8;
+        a_dst[i] = instr * 1024;
     }
-    // weight rows of instruction i: kr = (uw*NBI + i)*2 + (lane >> 5); kr & 3 depends on i's parity only
+    // ---- B loads.  Instruction covers 2 weight rows (2 x 512 bytes); weight row
+    // kr = (uw*NBI + i)*2 + (lane >> 5), and kr & 3 depends on i's parity only.
     const bf16_t *b_ptr[2];
 #pragma unroll
     for (int par = 0; par < 2; ++par) {
@@ -94,7 +115,7 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
 
     // ---- fragment read addresses
     const int a_rd_row = wm * 32 * C::MB + (lane & 31);
-    const int a_rd_swz = ((lane & 31) >> 1) & 7;
+    const int a_rd_swz = a_swz(lane & 31);  // tile rows are multiples of 32 apart: same swizzle
     const int a_rd_half = lane >> 5;
     int b_rd_col[C::NB];
 #pragma unroll
@@ -124,56 +145,109 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
         char *sa = smem + buf * C::STAGE;
         char *sb = sa + C::A_BYTES;
 #pragma unroll
-        for (int i = 0; i < NAI; ++i)
-            __builtin_amdgcn_global_load_lds(a_ptr[i] + kt * C::BK, (lds_void_t *)(sa + (uw * NAI + i) * 1024), 16, 0, 0);
+        for (int i = 0; i < C::NAI; ++i)
+            __builtin_amdgcn_global_load_lds(a_ptr[i] + kt * C::BK, (lds_void_t *)(sa + a_dst[i]), 16, 0, 0);
 #pragma unroll
-        for (int i = 0; i < NBI; ++i) {
-            const int r2 = (uw * NBI + i) * 2;  // first of the two weight rows of this instruction
+        for (int i = 0; i < C::NBI; ++i) {
+            const int r2 = (uw * C::NBI + i) * 2;  // first of the two weight rows of this instruction
             __builtin_amdgcn_global_load_lds(b_ptr[i & 1] + (size_t)(kt * C::BK + r2) * ldb,
                                              (lds_void_t *)(sb + r2 * (C::BN * 2)), 16, 0, 0);
         }
     };
-    auto wait_loads = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
-    auto compute = [&](int buf) {
+    constexpr int KK = C::BK / 16;  // MFMA reduction steps per stage
+    struct Frag {
+        bf16x8_t a[C::MB], b[C::NB];
+    };
+    auto load_frag = [&](int buf, int kk, Frag &f) {
         const char *sa = smem + buf * C::STAGE;
         const char *sb = sa + C::A_BYTES;
 #pragma unroll
-        for (int kk = 0; kk < C::BK / 16; ++kk) {
-            bf16x8_t af[C::MB], bfr[C::NB];
+        for (int mb = 0; mb < C::MB; ++mb) {
+            const int off = (a_rd_row + mb * 32) * C::A_ROW + ((((kk << 1) | a_rd_half) ^ a_rd_swz) << 4);
+            f.a[mb] = __builtin_bit_cast(bf16x8_t, *(const uint4 *)(sa + off));
+        }
 #pragma unroll
-            for (int mb = 0; mb < C::MB; ++mb) {
-                const int off = (a_rd_row + mb * 32) * 128 + ((((kk << 1) | a_rd_half) ^ a_rd_swz) << 4);
-                af[mb] = __builtin_bit_cast(bf16x8_t, *(const uint4 *)(sa + off));
-            }
-#pragma unroll
-            for (int nb = 0; nb < C::NB; ++nb) {
-                const int off = (kk * 16 + b_rd_row) * (C::BN * 2) + b_rd_col[nb];
-                s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (s16x4_t __attribute__((address_space(3))) *)(sb + off));
-                s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (s16x4_t __attribute__((address_space(3))) *)(sb + off + 4 * C::BN * 2));
-                s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                bfr[nb] = __builtin_bit_cast(bf16x8_t, v);
-            }
-#pragma unroll
-            for (int mb = 0; mb < C::MB; ++mb)
-#pragma unroll
-                for (int nb = 0; nb < C::NB; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[nb], af[mb], acc[mb][nb], 0, 0, 0);
+        for (int nb = 0; nb < C::NB; ++nb) {
+            const int off = (kk * 16 + b_rd_row) * (C::BN * 2) + b_rd_col[nb];
+            s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (s16x4_t __attribute__((address_space(3))) *)(sb + off));
+            s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (s16x4_t __attribute__((address_space(3))) *)(sb + off + 4 * C::BN * 2));
+            s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            f.b[nb] = __builtin_bit_cast(bf16x8_t, v);
         }
     };
+    auto mfma_all = [&](const Frag &f) {
+#pragma unroll
+        for (int mb = 0; mb < C::MB; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < C::NB; ++nb)
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[nb], f.a[mb], acc[mb][nb], 0, 0, 0);
+    };
+    // ask the scheduler to slot one LDS read behind each of the first MFMAs, so that
+    // the next step's fragments stream in underneath this step's matrix work
+    auto interleave = [&]() {
+        constexpr int NREAD = C::MB + 2 * C::NB, NMFMA = C::MB * C::NB;
+        constexpr int PAIRS = NREAD < NMFMA ? NREAD : NMFMA;
+#pragma unroll
+        for (int i = 0; i < PAIRS; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+        }
+        if (NMFMA > PAIRS) __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - PAIRS, 0);
+        if (NREAD > PAIRS) __builtin_amdgcn_sched_group_barrier(0x100, NREAD - PAIRS, 0);
+    };
 
+    // ---- pipeline.  NS stage buffers; loads run NS-1 stages ahead of the
+    // MFMAs.  A stage's buffer is free as soon as every wavefront has READ its
+    // last fragments (not when the MFMAs retire), so the barrier sits before the
+    // last MFMA step of the stage: behind it the refill loads and the first
+    // fragments of the next stage are issued, and their latency is covered by
+    // that last step.  Fragments are double-buffered in registers throughout.
     const int nk = K / C::BK;
-    issue_loads(0, 0);
-    wait_loads();
+#pragma unroll
+    for (int s = 0; s < C::NS; ++s)
+        if (s < nk) issue_loads(s, s);
+    if (nk >= C::NS)
+        wait_vmcnt<(C::NS - 1) * C::LPS>();
+    else
+        wait_vmcnt<0>();
     __syncthreads();
-    for (int kt = 0; kt < nk - 1; ++kt) {
-        issue_loads(kt + 1, (kt + 1) & 1);  // in flight while this stage is consumed
-        compute(kt & 1);
-        wait_loads();
-        __syncthreads();
+    Frag f0, f1;
+    load_frag(0, 0, f0);
+    int buf = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+        // steps 0 .. KK-2 of this stage: fetch step kk+1, multiply step kk
+#pragma unroll
+        for (int kk = 0; kk + 1 < KK; ++kk) {
+            if (kk & 1) {
+                load_frag(buf, kk + 1, f0);
+                mfma_all(f1);
+            } else {
+                load_frag(buf, kk + 1, f1);
+                mfma_all(f0);
+            }
+            interleave();
+        }
+        // last step: cross into the next stage first
+        Frag &last = ((KK - 1) & 1) ? f1 : f0;
+        Frag &first = ((KK - 1) & 1) ? f0 : f1;  // KK is even: the next stage starts in f0 again
+        const int nbuf = (buf + 1 == C::NS) ? 0 : buf + 1;
+        if (kt + 1 < nk) {
+            // stage kt+1 must have landed; stages kt+2 .. may stay in flight
+            if (kt + C::NS - 1 < nk)
+                wait_vmcnt<(C::NS - 2) * C::LPS>();
+            else
+                wait_vmcnt<0>();
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this stage's fragments are in registers
+            __syncthreads();
+            if (kt + C::NS < nk) issue_loads(kt + C::NS, buf);
+            load_frag(nbuf, 0, first);
+        }
+        mfma_all(last);
+        buf = nbuf;
     }
-    compute((nk - 1) & 1);
+    static_assert(KK % 2 == 0, "fragment double buffer assumes an even number of steps per stage");
     __syncthreads();
 
     // ---- epilogue: fp32 accumulators -> bf16 C tile in LDS.  Lane l holds, for
