@@ -24,8 +24,8 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 MFMA_BF16_PEAK_TF = 2500.0  # dense bf16 MFMA, published
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (profiles/megakernel_cfg2_pmc.txt), keyed by workload; None = not measured.
-MEASURED_TRAFFIC_BYTES = {}
+# (profiles/megakernel_cfg2_hbm_traffic.txt), keyed by workload; None = not measured.
+MEASURED_TRAFFIC_BYTES = {"cfg2": 3.232e9}
 
 
 def algorithmic_bytes(cfg) -> int:
