@@ -52,7 +52,7 @@ struct TileCfg {
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
     static_assert(BN == 256, "weight tile rows are 512 bytes");
     static_assert(BK == 32 || BK == 64, "stage depth");
-    static_assert((NS - 2) * LPS <= 63, "vmcnt range");
+    static_assert((NS - 1) * LPS <= 63, "vmcnt range");
 };
 
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
@@ -140,19 +140,33 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
 
-    typedef __attribute__((address_space(3))) void lds_void_t;
-    auto issue_loads = [&](int kt, int buf) {
-        char *sa = smem + buf * C::STAGE;
-        char *sb = sa + C::A_BYTES;
-#pragma unroll
-        for (int i = 0; i < C::NAI; ++i)
-            __builtin_amdgcn_global_load_lds(a_ptr[i] + kt * C::BK, (lds_void_t *)(sa + a_dst[i]), 16, 0, 0);
-#pragma unroll
-        for (int i = 0; i < C::NBI; ++i) {
-            const int r2 = (uw * C::NBI + i) * 2;  // first of the two weight rows of this instruction
-            __builtin_amdgcn_global_load_lds(b_ptr[i & 1] + (size_t)(kt * C::BK + r2) * ldb,
-                                             (lds_void_t *)(sb + r2 * (C::BN * 2)), 16, 0, 0);
+    // load number i (0 .. LPS-1) of stage kt into stage buffer buf.  Written as
+    // inline assembly on purpose: the compiler tracks its own LDS-DMA loads and,
+    // unable to prove that a later ds_read touches another buffer, puts
+    // s_waitcnt vmcnt(0) in front of the next LDS read, which serialises the
+    // whole pipeline.  Here the waits are placed by hand (wait_vmcnt below).
+    // M0 carries the LDS byte address of the 1 KB destination.
+    const u32 lds_base = (u32)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
+    auto dma16 = [&](const bf16_t *src, u32 lds_addr) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                     :
+                     : "s"(lds_addr), "v"(src)
+                     : "m0");
+    };
+    auto issue_one = [&](int kt, int buf, int i) {
+        const u32 sa = lds_base + buf * C::STAGE;
+        const u32 sb = sa + C::A_BYTES;
+        if (i < C::NAI) {
+            dma16(a_ptr[i] + kt * C::BK, sa + a_dst[i]);
+        } else {
+            const int j = i - C::NAI;
+            const int r2 = (uw * C::NBI + j) * 2;  // first of the two weight rows of this instruction
+            dma16(b_ptr[j & 1] + (size_t)(kt * C::BK + r2) * ldb, sb + r2 * (C::BN * 2));
         }
+    };
+    auto issue_loads = [&](int kt, int buf) {
+#pragma unroll
+        for (int i = 0; i < C::LPS; ++i) issue_one(kt, buf, i);
     };
     constexpr int KK = C::BK / 16;  // MFMA reduction steps per stage
     struct Frag {
@@ -184,70 +198,85 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
             for (int nb = 0; nb < C::NB; ++nb)
                 acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[nb], f.a[mb], acc[mb][nb], 0, 0, 0);
     };
-    // ask the scheduler to slot one LDS read behind each of the first MFMAs, so that
-    // the next step's fragments stream in underneath this step's matrix work
-    auto interleave = [&]() {
-        constexpr int NREAD = C::MB + 2 * C::NB, NMFMA = C::MB * C::NB;
-        constexpr int PAIRS = NREAD < NMFMA ? NREAD : NMFMA;
+    // One MFMA step of the software pipeline: fetch the fragments `nxt` of the
+    // step after, issue a share of the refill loads, multiply with `cur`.  A burst
+    // of global->LDS loads blocks the wavefront for as long as the texture path
+    // takes to accept it (about 2000 cycles for a whole 256 x 256 stage), so the
+    // loads are dealt out over the steps and the scheduler is asked to interleave:
+    // one LDS read behind each MFMA, one global load every few MFMAs.
+    constexpr int LPK = (C::LPS + KK - 1) / KK;  // refill loads per step
+    constexpr int NREAD = C::MB + 2 * C::NB, NMFMA = C::MB * C::NB;
+    auto step = [&](int frag_buf, int frag_kk, Frag &nxt, const Frag &cur, int fill_kt, int fill_buf, int part) {
+        load_frag(frag_buf, frag_kk, nxt);
 #pragma unroll
-        for (int i = 0; i < PAIRS; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+        for (int mb = 0; mb < C::MB; ++mb)
+#pragma unroll
+            for (int nb = 0; nb < C::NB; ++nb) {
+                const int i = mb * C::NB + nb;
+                // share j of this step's loads goes in front of MFMA number j*NMFMA/LPK
+#pragma unroll
+                for (int j = 0; j < LPK; ++j)
+                    if ((j * NMFMA) / LPK == i && part * LPK + j < C::LPS) issue_one(fill_kt, fill_buf, part * LPK + j);
+                acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.b[nb], cur.a[mb], acc[mb][nb], 0, 0, 0);
+            }
+#pragma unroll
+        for (int i = 0; i < NMFMA; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // one MFMA
+            if (i < NREAD) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
         }
-        if (NMFMA > PAIRS) __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - PAIRS, 0);
-        if (NREAD > PAIRS) __builtin_amdgcn_sched_group_barrier(0x100, NREAD - PAIRS, 0);
+        if (NREAD > NMFMA) __builtin_amdgcn_sched_group_barrier(0x100, NREAD - NMFMA, 0);
     };
 
     // ---- pipeline.  NS stage buffers; loads run NS-1 stages ahead of the
     // MFMAs.  A stage's buffer is free as soon as every wavefront has READ its
     // last fragments (not when the MFMAs retire), so the barrier sits before the
-    // last MFMA step of the stage: behind it the refill loads and the first
-    // fragments of the next stage are issued, and their latency is covered by
-    // that last step.  Fragments are double-buffered in registers throughout.
+    // last MFMA step of the stage; the refill of that buffer (stage kt+NS) is dealt
+    // out over the KK steps that follow the barrier.  Past the end of K the refill
+    // re-loads the last stage into a buffer nobody reads any more: every wavefront
+    // then always has the same number of loads in flight and one vmcnt value fits
+    // every iteration.  Fragments are double-buffered in registers throughout.
     const int nk = K / C::BK;
+    // prologue: stages 0 .. NS-2 whole, plus the first share of stage NS-1 (its other
+    // shares ride on the first stage's MFMA steps like every later refill)
 #pragma unroll
-    for (int s = 0; s < C::NS; ++s)
-        if (s < nk) issue_loads(s, s);
-    if (nk >= C::NS)
-        wait_vmcnt<(C::NS - 1) * C::LPS>();
-    else
-        wait_vmcnt<0>();
+    for (int s = 0; s + 1 < C::NS; ++s) issue_loads(min(s, nk - 1), s);
+    int fill_kt = min(C::NS - 1, nk - 1), fill_buf = C::NS - 1;
+    constexpr int PART0 = LPK < C::LPS ? LPK : C::LPS;
+#pragma unroll
+    for (int i = 0; i < PART0; ++i) issue_one(fill_kt, fill_buf, i);
+    wait_vmcnt<(C::NS - 2) * C::LPS + PART0>();
     __syncthreads();
     Frag f0, f1;
     load_frag(0, 0, f0);
     int buf = 0;
-    for (int kt = 0; kt < nk; ++kt) {
-        // steps 0 .. KK-2 of this stage: fetch step kk+1, multiply step kk
+    static_assert(KK % 2 == 0, "fragment double buffer assumes an even number of steps per stage");
+    // steps 0 .. KK-2 of a stage; they also carry shares 1 .. KK-1 of the refill in progress
+    auto main_steps = [&](int b) {
 #pragma unroll
         for (int kk = 0; kk + 1 < KK; ++kk) {
-            if (kk & 1) {
-                load_frag(buf, kk + 1, f0);
-                mfma_all(f1);
-            } else {
-                load_frag(buf, kk + 1, f1);
-                mfma_all(f0);
-            }
-            interleave();
-        }
-        // last step: cross into the next stage first
-        Frag &last = ((KK - 1) & 1) ? f1 : f0;
-        Frag &first = ((KK - 1) & 1) ? f0 : f1;  // KK is even: the next stage starts in f0 again
-        const int nbuf = (buf + 1 == C::NS) ? 0 : buf + 1;
-        if (kt + 1 < nk) {
-            // stage kt+1 must have landed; stages kt+2 .. may stay in flight
-            if (kt + C::NS - 1 < nk)
-                wait_vmcnt<(C::NS - 2) * C::LPS>();
+            if (kk & 1)
+                step(b, kk + 1, f0, f1, fill_kt, fill_buf, kk + 1);
             else
-                wait_vmcnt<0>();
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this stage's fragments are in registers
-            __syncthreads();
-            if (kt + C::NS < nk) issue_loads(kt + C::NS, buf);
-            load_frag(nbuf, 0, first);
+                step(b, kk + 1, f1, f0, fill_kt, fill_buf, kk + 1);
         }
-        mfma_all(last);
+    };
+    // KK is even: a stage starts in f0 and its last step multiplies f1
+    for (int kt = 0; kt + 1 < nk; ++kt) {
+        main_steps(buf);
+        // last step of the stage: cross into the next stage first.  Stage kt+1 must
+        // have landed; the NS-2 stages issued after it may stay in flight.
+        wait_vmcnt<(C::NS - 2) * C::LPS>();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this stage's fragments are in registers
+        __syncthreads();
+        const int nbuf = (buf + 1 == C::NS) ? 0 : buf + 1;
+        fill_kt = min(kt + C::NS, nk - 1);
+        fill_buf = buf;
+        step(nbuf, 0, f0, f1, fill_kt, fill_buf, 0);
         buf = nbuf;
     }
-    static_assert(KK % 2 == 0, "fragment double buffer assumes an even number of steps per stage");
+    main_steps(buf);
+    mfma_all(f1);
+    wait_vmcnt<0>();  // nothing may still be landing in LDS when the C tile is written over the stage buffers
     __syncthreads();
 
     // ---- epilogue: fp32 accumulators -> bf16 C tile in LDS.  Lane l holds, for
