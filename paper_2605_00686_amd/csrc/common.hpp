@@ -165,6 +165,16 @@ __device__ __forceinline__ void mark_phase_end(Ctrl *c, int phase) {
     atomicMax(&c->stats[8 + phase], now_ticks() - t0);
 }
 
+// Tell the compiler that a value is the same in every lane (function arguments
+// of non-inlined device functions arrive in vector registers).
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+template <typename T>
+__device__ __forceinline__ T *uniform(T *p) {
+    const u64 v = (u64)p;
+    const u32 lo = __builtin_amdgcn_readfirstlane((u32)v), hi = __builtin_amdgcn_readfirstlane((u32)(v >> 32));
+    return (T *)(((u64)hi << 32) | lo);
+}
+
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((u32)b) << 16); }
 // round to nearest even; inputs here are finite
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {

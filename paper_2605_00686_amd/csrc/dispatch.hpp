@@ -9,12 +9,12 @@ namespace moe {
 
 // LDS the plan needs, and whether its two tables are staged in LDS (they are
 // unless the problem is unusually large; then the slow global-memory path runs).
-constexpr size_t kPlanSegLds = 32 * 1024, kPlanHistLds = 32 * 1024;
-__host__ __device__ inline bool plan_seg_in_lds(int E, int R) { return (size_t)2 * E * R * 4 <= kPlanSegLds; }
+constexpr size_t kPlanSegLds = 48 * 1024, kPlanHistLds = 32 * 1024;
+__host__ __device__ inline bool plan_seg_in_lds(int E, int R) { return (size_t)3 * E * R * 4 <= kPlanSegLds; }
 __host__ __device__ inline bool plan_hist_in_lds(int nPB, int E) { return (size_t)nPB * E * 4 <= kPlanHistLds; }
 __host__ __device__ inline size_t plan_smem_bytes(int E, int R, int nPB) {
     size_t n = (size_t)(3 * E + R + 8) * 4;
-    if (plan_seg_in_lds(E, R)) n += (size_t)2 * E * R * 4;
+    if (plan_seg_in_lds(E, R)) n += (size_t)3 * E * R * 4;
     if (plan_hist_in_lds(nPB, E)) n += (size_t)nPB * E * 4;
     return n;
 }
@@ -33,11 +33,14 @@ __device__ void plan_task(const KArgs &a, char *smem) {
     int32_t *s_rb = s_dest + R + 1;    // [E+1]
     int32_t *s_free = s_rb + E + 2;
     const bool seg_lds = plan_seg_in_lds(E, R), hist_lds = plan_hist_in_lds(nPB, E);
-    int32_t *segc = a.seg_cnt, *segb = a.seg_begin, *hist = a.blk_base;
+    int32_t *segc = a.seg_cnt, *segb = a.seg_begin, *hist = a.blk_base, *nfl = a.flag_base;
+    // tile_m and the row-block height are powers of two
+    const int lm = 31 - __clz(a.tile_m), lbm = 31 - __clz(a.tl.BM);
     if (seg_lds) {
         segc = s_free;
         segb = segc + E * R;
-        s_free = segb + E * R;
+        nfl = segb + E * R;  // [R][E]
+        s_free = nfl + E * R;
         for (int q = tid; q < E * R; q += kThreads) segc[q] = a.seg_cnt[q];
     }
     if (hist_lds) {
@@ -64,7 +67,7 @@ __device__ void plan_task(const KArgs &a, char *smem) {
             s_off[e] = run;
             s_rb[e] = rb;
             run += s_cnt[e];
-            rb += (s_cnt[e] + a.tl.BM - 1) / a.tl.BM;
+            rb += (s_cnt[e] + a.tl.BM - 1) >> lbm;
         }
         s_off[E] = run;
         s_rb[E] = rb;
@@ -89,17 +92,27 @@ __device__ void plan_task(const KArgs &a, char *smem) {
         }
     }
     // flags: destination-major, then expert; a segment with expert-local rows
-    // [b0, b0+c) touches row blocks b0/tile_m .. (b0+c-1)/tile_m
-    for (int r = tid; r < R; r += kThreads) {
+    // [b0, b0+c) touches row blocks b0/tile_m .. (b0+c-1)/tile_m.  All (r, e)
+    // pairs in parallel, then one short scan per destination.
+    for (int q = tid; q < E * R; q += kThreads) {
+        const int r = q / E, e = q - r * E;
+        const int c = segc[e * R + r];
         int n = 0;
-        for (int e = 0; e < E; ++e) {
-            const int c = segc[e * R + r];
-            if (c > 0) {
-                const int b0 = segb[e * R + r];
-                n += ((b0 + c - 1) / a.tile_m - b0 / a.tile_m + 1) * a.ncb;
-            }
+        if (c > 0) {
+            const int b0 = segb[e * R + r];
+            n = (((b0 + c - 1) >> lm) - (b0 >> lm) + 1) * a.ncb;
         }
-        s_dest[r] = n;
+        nfl[q] = n;
+    }
+    __syncthreads();
+    for (int r = tid; r < R; r += kThreads) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) {
+            const int n = nfl[r * E + e];
+            nfl[r * E + e] = run;  // exclusive within the destination
+            run += n;
+        }
+        s_dest[r] = run;
     }
     __syncthreads();
     if (tid == 0) {
@@ -117,20 +130,8 @@ __device__ void plan_task(const KArgs &a, char *smem) {
         for (int q = tid; q < nPB * E; q += kThreads) a.blk_base[q] = hist[q];
     if (seg_lds)
         for (int q = tid; q < E * R; q += kThreads) a.seg_begin[q] = segb[q];
-    for (int r = tid; r <= R; r += kThreads) {
-        a.dest_flag_begin[r] = s_dest[r];
-        if (r < R) {
-            int run = s_dest[r];
-            for (int e = 0; e < E; ++e) {
-                a.flag_base[(size_t)r * E + e] = run;
-                const int c = segc[e * R + r];
-                if (c > 0) {
-                    const int b0 = segb[e * R + r];
-                    run += ((b0 + c - 1) / a.tile_m - b0 / a.tile_m + 1) * a.ncb;
-                }
-            }
-        }
-    }
+    for (int q = tid; q < E * R; q += kThreads) a.flag_base[q] = nfl[q] + s_dest[q / E];
+    for (int r = tid; r <= R; r += kThreads) a.dest_flag_begin[r] = s_dest[r];
     __syncthreads();
 }
 

@@ -87,8 +87,13 @@ __device__ __forceinline__ TileInfo decode_tile(const KArgs &a, const Tables &tb
 // Rows are gathered straight from x through perm: the permuted activations are
 // never materialised.
 template <class P>
-__device__ void g1_tile(const KArgs &a, const Tables &tb, int lt, char *smem) {
+__device__ __attribute__((noinline)) void g1_tile(const KArgs &a_in, const Tables &tb_in, int lt, char *smem) {
     using ET = typename P::ET;
+    // private copies: the caller's objects live in memory (this function is not inlined, so
+    // that the GEMM gets a register allocation of its own), and every global store below
+    // would otherwise force their fields to be re-read
+    const KArgs a = a_in;
+    const Tables tb = tb_in;
     const TileInfo ti = decode_tile(a, tb, lt, a.tl.NT1, P::BN1, a.f);
     if (!ti.valid) return;
     const ET *x = (const ET *)a.x;
@@ -239,8 +244,10 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
 // staging row perm[p] (the slot that asked for it).  The caller has already
 // waited for the block's h rows.
 template <class P>
-__device__ void g2_tile(const KArgs &a, const TileInfo &ti, char *smem) {
+__device__ __attribute__((noinline)) void g2_tile(const KArgs &a_in, const TileInfo &ti_in, char *smem) {
     using ET = typename P::ET;
+    const KArgs a = a_in;  // private copies, see g1_tile
+    const TileInfo ti = ti_in;
     const ET *h = (const ET *)a.h;
     auto rowptr = [&](int r) { return h + (size_t)(ti.row0 + min(r, ti.nrows - 1)) * a.f; };
     const ET *B0 = (const ET *)a.W2 + (size_t)ti.e * a.f * a.d + ti.n0;

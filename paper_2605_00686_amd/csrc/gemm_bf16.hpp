@@ -148,9 +148,10 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
     // M0 carries the LDS byte address of the 1 KB destination.
     const u32 lds_base = (u32)(uintptr_t)(__attribute__((address_space(3))) char *)smem;
     auto dma16 = [&](const bf16_t *src, u32 lds_addr) {
+        // the address is uniform by construction; make the compiler see it as scalar
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                      :
-                     : "s"(lds_addr), "v"(src)
+                     : "s"(__builtin_amdgcn_readfirstlane(lds_addr)), "v"(src)
                      : "m0");
     };
     auto issue_one = [&](int kt, int buf, int i) {

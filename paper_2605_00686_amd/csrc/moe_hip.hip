@@ -153,7 +153,13 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
         } else if (task < a.t_g2) {
             phase = 3;
             need_perm();
-            if (!bad) g1_tile<P>(a, tb, task - a.t_g1, smem);
+            if (!bad) {
+                // the tile functions are real calls: hand them copies, so that the kernel's own
+                // argument block and tables never have their address taken and stay in registers
+                const KArgs ac = a;
+                const Tables tc = tb;
+                g1_tile<P>(ac, tc, task - a.t_g1, smem);
+            }
         } else if (task < a.t_comb) {
             phase = 4;
             need_plan();
@@ -163,7 +169,11 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
             if (ti.valid) {  // uniform: every thread decodes the same tile
                 if (tid == 0) s_ok = wait_ge(c, &a.h_ready[ti.rb], (u32)a.tl.NT1) ? 1 : 0;
                 __syncthreads();
-                if (s_ok) g2_tile<P>(a, ti, smem);
+                if (s_ok) {
+                    const KArgs ac = a;
+                    const TileInfo tic = ti;
+                    g2_tile<P>(ac, tic, smem);
+                }
             }
         } else {
             phase = 5;

@@ -25,19 +25,23 @@ struct RouteLoad;
 template <>
 struct RouteLoad<bf16_t> {
     typedef uint2 x4_t;  // four consecutive bf16
+    typedef u32 raw_t;   // one bf16 in the low half
     static __device__ __forceinline__ double get(const x4_t &v, int s) {
         const u32 w = (s < 2) ? v.x : v.y;
         return (double)__uint_as_float((s & 1) ? (w & 0xffff0000u) : (w << 16));
     }
-    static __device__ __forceinline__ double one(const bf16_t *p) { return (double)bf16_to_f32(*p); }
+    static __device__ __forceinline__ raw_t load_raw(const bf16_t *p) { return (u32)*p; }
+    static __device__ __forceinline__ double to_double(raw_t r) { return (double)__uint_as_float(r << 16); }
 };
 template <>
 struct RouteLoad<float> {
     typedef float4 x4_t;
+    typedef float raw_t;
     static __device__ __forceinline__ double get(const x4_t &v, int s) {
         return (double)(s == 0 ? v.x : s == 1 ? v.y : s == 2 ? v.z : v.w);
     }
-    static __device__ __forceinline__ double one(const float *p) { return (double)*p; }
+    static __device__ __forceinline__ raw_t load_raw(const float *p) { return *p; }
+    static __device__ __forceinline__ double to_double(raw_t r) { return (double)r; }
 };
 
 // Logits of tokens [t0, t0+16) into lg[16][E] (LDS, fp64) with the fp64 matrix
@@ -47,9 +51,14 @@ struct RouteLoad<float> {
 // (or expert) l % 16 and reduction index 4*(l / 16) + s within a chunk of 16;
 // the four wavefronts take contiguous quarters of the reduction and add their
 // partial sums into LDS one after the other (fixed order: deterministic).
-template <typename ET, int NB>
+// NB expert blocks of 16 starting at block eb0; U chunks of 16 per iteration,
+// the operands of the next iteration are in flight while this one multiplies
+// (U * NB is kept near 8 so that an iteration hides a trip to L2).
+template <typename ET, int NB, int U>
 __device__ void route_logits(const KArgs &a, int t0, int eb0, char *smem) {
     typedef RouteLoad<ET> L;
+    typedef typename L::x4_t x4_t;
+    typedef typename L::raw_t raw_t;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int E = a.E, d = a.d;
     const int li = lane & 15, kq = lane >> 4;
@@ -60,26 +69,58 @@ __device__ void route_logits(const KArgs &a, int t0, int eb0, char *smem) {
     const int c_begin = (nchunk * wave) / 4, c_end = (nchunk * (wave + 1)) / 4;
     const int tok = min(t0 + li, a.T - 1);
     const ET *xrow = x + (size_t)tok * d + 4 * kq;
+    // expert column of this lane in block eb0 + eb; lanes past E re-read a valid column and are masked
+    bool live[NB];
+    const ET *wcol[NB];
+#pragma unroll
+    for (int eb = 0; eb < NB; ++eb) {
+        const int e = (eb0 + eb) * 16 + li;
+        live[eb] = e < E;
+        wcol[eb] = Wg + (size_t)(4 * kq) * E + (live[eb] ? e : 0);
+    }
 
     f64x4_t acc[NB];
 #pragma unroll
     for (int eb = 0; eb < NB; ++eb) acc[eb] = f64x4_t{0.0, 0.0, 0.0, 0.0};
-    // expert column of this lane in block eb0 + eb; lanes past E feed zeros
-    const ET *wcol = Wg + (size_t)(4 * kq) * E + eb0 * 16 + li;
 
-    for (int c = c_begin; c < c_end; ++c) {
-        const typename L::x4_t xv = *(const typename L::x4_t *)(xrow + c * 16);
-        const ET *wrow = wcol + (size_t)(c * 16) * E;
+    struct Raw {
+        x4_t xv[U];
+        raw_t w[U][4][NB];
+    };
+    auto load = [&](int c0, Raw &r) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const double av = L::get(xv, s);
-            double bv[NB];
+        for (int u = 0; u < U; ++u) {
+            const int c = min(c0 + u, c_end - 1);  // past the end: re-read the last chunk, masked in mul()
+            r.xv[u] = *(const x4_t *)(xrow + c * 16);
 #pragma unroll
-            for (int eb = 0; eb < NB; ++eb)
-                bv[eb] = ((eb0 + eb) * 16 + li < E) ? L::one(wrow + (size_t)s * E + eb * 16) : 0.0;
+            for (int s = 0; s < 4; ++s)
 #pragma unroll
-            for (int eb = 0; eb < NB; ++eb)
-                acc[eb] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv[eb], acc[eb], 0, 0, 0);
+                for (int eb = 0; eb < NB; ++eb) r.w[u][s][eb] = L::load_raw(wcol[eb] + (size_t)(c * 16 + s) * E);
+        }
+    };
+    auto mul = [&](int c0, const Raw &r) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool in = c0 + u < c_end;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const double av = in ? L::get(r.xv[u], s) : 0.0;
+#pragma unroll
+                for (int eb = 0; eb < NB; ++eb) {
+                    const double bv = live[eb] ? L::to_double(r.w[u][s][eb]) : 0.0;
+                    acc[eb] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[eb], 0, 0, 0);
+                }
+            }
+        }
+    };
+    Raw r0, r1;
+    if (c_begin < c_end) {
+        load(c_begin, r0);
+        for (int c = c_begin; c < c_end; c += 2 * U) {
+            load(c + U, r1);
+            mul(c, r0);
+            load(c + 2 * U, r0);
+            mul(c + U, r1);
         }
     }
     // D layout: lane l, register v -> token 4*v + l/16, expert (block) l % 16
@@ -106,13 +147,13 @@ template <typename ET>
 __device__ void route_logits_dispatch(const KArgs &a, int t0, char *smem) {
     const int nb = (a.E + 15) / 16;
     if (nb <= 1)
-        route_logits<ET, 1>(a, t0, 0, smem);
+        route_logits<ET, 1, 8>(a, t0, 0, smem);
     else if (nb <= 2)
-        route_logits<ET, 2>(a, t0, 0, smem);
+        route_logits<ET, 2, 4>(a, t0, 0, smem);
     else if (nb <= 4)
-        route_logits<ET, 4>(a, t0, 0, smem);
+        route_logits<ET, 4, 2>(a, t0, 0, smem);
     else
-        for (int eb0 = 0; eb0 < nb; eb0 += 8) route_logits<ET, 8>(a, t0, eb0, smem);  // 128 experts per pass
+        for (int eb0 = 0; eb0 < nb; eb0 += 8) route_logits<ET, 8, 1>(a, t0, eb0, smem);  // 128 experts per pass
 }
 
 // One gate task: tokens [task*16, task*16+16).  With a.Wg == NULL the routing
