@@ -30,9 +30,14 @@ struct Ctrl {
     u32 error;       // first device status (moe_status_t as positive number), 0 = ok
     u32 n_rb;        // row blocks in use (all experts)
     u32 n_flags;     // publish tiles / flags in use
-    u32 pad[8];
+    u32 tile_next[8];  // per-XCD tile queues: next entry to hand out
+    u32 comb_next;     // next combine task
+    u32 pad[7];
     u64 t0;          // wall-clock tick of the first task drawn
     u64 stats[MOE_NUM_STATS];
+#ifdef MOE_TILE_TIMING
+    u64 dbg[32];  // development build only: time spent in the parts of a tile, summed over tiles
+#endif
 };
 
 // GEMM tiling chosen on the host.
@@ -54,8 +59,9 @@ struct KArgs {
     int nPB, nRT, nCT;     // permutation blocks, gate tasks, combine tasks
     int comb_tokens;       // tokens per combine task
     Tiling tl;
-    // task ranges of the persistent scheduler: [route | plan | perm | g1 | g2 | combine)
-    int t_plan, t_perm, t_g1, t_g2, t_comb, t_end;
+    // front task ranges of the persistent scheduler: [route | plan | perm), then the tile
+    // queues and the combine tasks; t_end bounds the useful number of workgroups
+    int t_plan, t_perm, t_g1, t_end;
     // caller tensors
     const void *x, *Wg;
     const float *bias;
@@ -84,6 +90,7 @@ struct KArgs {
     void *h;                   // [N][f]
     size_t zero_bytes;         // bytes from ctrl that must be zero between calls
     int tab_lds_off;           // megakernel: LDS offset of the cached decode tables, 0 = none
+    int sched_lds_off;         // megakernel: LDS offset of the tile loop's broadcast slots (16 bytes)
 };
 
 __device__ __forceinline__ u64 now_ticks() { return wall_clock64(); }
@@ -118,6 +125,19 @@ __device__ __forceinline__ void fence_acquire(int system_scope) {
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 }
 
+// Acquire without cache invalidation, for data with these three properties:
+// it is written once per launch, its writer made it visible with a device-scope
+// release before the counter or flag that was just observed, and nothing reads
+// its address earlier in the launch.  Then no cache of this XCD can hold a
+// stale copy (caches start a launch empty), and the loads that follow fetch
+// what the writer released.  The fence only keeps the compiler and the
+// wavefront from moving those loads up.  A device-scope acquire would do the
+// same and also invalidate the XCD's whole L2, which the other workgroups of
+// the XCD are using to share weight tiles.
+__device__ __forceinline__ void fence_acquire_no_invalidate() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
 // Workgroup barrier that also waits for this wavefront's outstanding global
 // stores.  __syncthreads() alone only drains LDS traffic; a store still in
 // flight when ANOTHER wavefront of the workgroup issues the release fence would
@@ -129,10 +149,15 @@ __device__ __forceinline__ void sync_stores() {
 
 // Spin until *p >= target (agent scope), bounded by the wall clock and by the
 // global error flag so that a broken dependency drains the grid instead of
-// hanging it.  Called by one thread; returns false on time-out.
+// hanging it.  Called by one thread; returns false on time-out.  INVALIDATE
+// false: see fence_acquire_no_invalidate().
+template <bool INVALIDATE = true>
 __device__ __forceinline__ bool wait_ge(Ctrl *c, const u32 *p, u32 target) {
     if (ld_relaxed_agent(p) >= target) {
-        fence_acquire(0);
+        if (INVALIDATE)
+            fence_acquire(0);
+        else
+            fence_acquire_no_invalidate();
         return true;
     }
     const u64 t0 = now_ticks();
@@ -155,7 +180,12 @@ __device__ __forceinline__ bool wait_ge(Ctrl *c, const u32 *p, u32 target) {
         }
     }
     atomicAdd(&c->stats[14], now_ticks() - t0);
-    if (ok) fence_acquire(0);
+    if (ok) {
+        if (INVALIDATE)
+            fence_acquire(0);
+        else
+            fence_acquire_no_invalidate();
+    }
     return ok;
 }
 
@@ -165,15 +195,67 @@ __device__ __forceinline__ void mark_phase_end(Ctrl *c, int phase) {
     atomicMax(&c->stats[8 + phase], now_ticks() - t0);
 }
 
-// Tell the compiler that a value is the same in every lane (function arguments
-// of non-inlined device functions arrive in vector registers).
-__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+#ifdef MOE_TILE_TIMING
+#define MOE_TT_BEGIN() u64 tt_prev_ = now_ticks()
+#define MOE_TT(ctrl, slot)                                     \
+    do {                                                       \
+        const u64 tt_now_ = now_ticks();                       \
+        if (threadIdx.x == 0) atomicAdd(&(ctrl)->dbg[slot], tt_now_ - tt_prev_); \
+        tt_prev_ = tt_now_;                                    \
+    } while (0)
+#else
+#define MOE_TT_BEGIN() do {} while (0)
+#define MOE_TT(ctrl, slot) do {} while (0)
+#endif
+
+// Device functions that are real calls (not inlined) cannot see where a pointer
+// they are handed points.  These helpers tell the compiler, so that it emits
+// global_* / ds_* instead of the slower flat_* instructions.
 template <typename T>
-__device__ __forceinline__ T *uniform(T *p) {
-    const u64 v = (u64)p;
-    const u32 lo = __builtin_amdgcn_readfirstlane((u32)v), hi = __builtin_amdgcn_readfirstlane((u32)(v >> 32));
-    return (T *)(((u64)hi << 32) | lo);
+__device__ __forceinline__ T *as_global(T *p) {
+    return (T *)(__attribute__((address_space(1))) T *)p;
 }
+__device__ __forceinline__ char *lds_at(u32 byte_offset) {
+    return (char *)(__attribute__((address_space(3))) char *)(uintptr_t)byte_offset;
+}
+__device__ __forceinline__ u32 lds_offset(const void *p) {
+    return (u32)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
+}
+// The argument block of the running kernel sits in constant memory that scalar
+// loads can read.  A kernel whose single parameter is a KArgs takes its address
+// with kernel_args_address() (the compiler only knows it inside the kernel
+// function itself) and hands it to device functions that are real calls; those
+// read the block with load_kernel_args(): a handful of scalar loads instead of a
+// copy through per-lane scratch memory.
+typedef u64 KArgsAddr;
+__device__ __forceinline__ KArgsAddr kernel_args_address() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (KArgsAddr)(uintptr_t)__builtin_amdgcn_kernarg_segment_ptr();
+#else
+    return 0;
+#endif
+}
+__device__ __forceinline__ KArgs load_kernel_args(KArgsAddr addr) {
+    KArgs a;
+#if defined(__HIP_DEVICE_COMPILE__)
+    const u32 lo = __builtin_amdgcn_readfirstlane((u32)addr), hi = __builtin_amdgcn_readfirstlane((u32)(addr >> 32));
+    // (an aligned pointer to constant memory at a uniform address: the copy becomes scalar loads)
+    typedef const __attribute__((address_space(4))) KArgs *ConstArgs;
+    __builtin_memcpy(&a, (ConstArgs)(uintptr_t)(((u64)hi << 32) | lo), sizeof(KArgs));
+#endif
+    return a;
+}
+// A value known to be the same in every lane, moved to a scalar register.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Which of the chip's XCDs (accelerator dies, each with an L2 of its own) this
+// wavefront runs on.
+__device__ __forceinline__ int xcd_id() {
+    u32 v;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(v));
+    return (int)(v & 0xfu);
+}
+constexpr int kTileQueues = 8;  // one per XCD of an MI355X
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float(((u32)b) << 16); }
 // round to nearest even; inputs here are finite

@@ -15,7 +15,7 @@ struct Bf16Policy {
     static constexpr int BM = C::BM, BN1 = C::BN / 2, BN2 = C::BN;
     static constexpr int C_STRIDE = C::C_STRIDE;
     static constexpr int SMEM_MAIN = C::SMEM_MAIN;
-    static constexpr int MIN_WAVES = (C::BM <= 32) ? 2 : 1;  // wavefronts per SIMD the kernel is built for
+    static constexpr int MIN_WAVES = (C::BM <= 128) ? 2 : 1;  // wavefronts per SIMD the kernel is built for
     template <bool GATED, class RowPtr>
     static __device__ __forceinline__ void gemm(RowPtr rp, const ET *B0, const ET *B1, int ldb, int ncols, int K,
                                                 char *smem) {
@@ -42,7 +42,7 @@ constexpr int tile_smem_bytes() {
 
 // stage depth / count per shape: the best of the variants measured on MI355X
 using CfgL = TileCfg<4, 4, 2, 2, 32, 4>;  // 256 x 256, wavefront 128 x 128
-using CfgM = TileCfg<2, 4, 2, 2, 64, 3>;  // 128 x 256, wavefront  64 x 128
+using CfgM = TileCfg<2, 4, 2, 2, 32, 3>;  // 128 x 256, wavefront  64 x 128, two workgroups per CU
 using CfgS = TileCfg<1, 2, 1, 4, 64, 2>;  //  32 x 256, wavefront  32 x  64, two workgroups per CU
 
 struct TileInfo {
@@ -57,24 +57,41 @@ struct Tables {
     int n_rb;
 };
 
-// Task -> tile.  Tiles of one expert are consecutive; inside an expert the
-// column tile varies slowest, so tiles running at the same time share one
-// weight column block and the expert's rows (the re-read operand is the small
-// one and stays in cache).
-__device__ __forceinline__ TileInfo decode_tile(const KArgs &a, const Tables &tb, int lt, int NT, int BN,
-                                                int total_cols) {
+// The row blocks [0, n_rb) of all experts, in expert order, are cut into
+// kTileQueues contiguous shares, one per XCD.  The queue of a share lists its
+// GEMM1 tiles, then its GEMM2 tiles; workgroups draw from the queue of the XCD
+// they run on (and from the others once it is empty).  Tiles that read the same
+// weights or the same rows therefore meet in one L2 instead of fetching the
+// operand once per XCD, and a GEMM2 tile only depends on entries that come
+// before it in its own queue.
+struct TileQueue {
+    int r0, r1;  // row blocks of this share
+    int n1, n2;  // GEMM1 / GEMM2 tiles
+};
+__device__ __forceinline__ TileQueue tile_queue(const KArgs &a, int n_rb, int q) {
+    TileQueue tq;
+    tq.r0 = (int)(((long long)n_rb * q) / kTileQueues);
+    tq.r1 = (int)(((long long)n_rb * (q + 1)) / kTileQueues);
+    tq.n1 = (tq.r1 - tq.r0) * a.tl.NT1;
+    tq.n2 = (tq.r1 - tq.r0) * a.tl.NT2;
+    return tq;
+}
+
+// Entry i of one phase of a queue -> tile.  Inside the share, the tiles of one
+// expert are consecutive and the column tile varies slowest, so tiles running
+// at the same time share one weight column block and the expert's rows.
+__device__ __forceinline__ TileInfo decode_tile(const KArgs &a, const Tables &tb, const TileQueue &tq, int i, int NT,
+                                                int BN, int total_cols) {
     TileInfo ti;
-    ti.valid = false;
-    const int vrb = lt / NT;
-    if (vrb >= tb.n_rb) return ti;
-    const int e = tb.rb_expert[vrb];
-    const int base = tb.rb_base[e];
-    const int nrb = tb.rb_base[e + 1] - base;
-    const int loc = lt - base * NT;
+    const int e = tb.rb_expert[tq.r0 + i / NT];
+    const int e_rb0 = tb.rb_base[e];
+    const int s0 = max(e_rb0, tq.r0), s1 = min(tb.rb_base[e + 1], tq.r1);  // the expert's row blocks in this share
+    const int nrb = s1 - s0;
+    const int loc = i - (s0 - tq.r0) * NT;
     const int ct = loc / nrb, rbl = loc % nrb;
     ti.e = e;
-    ti.rb = base + rbl;
-    ti.lrow0 = rbl * a.tl.BM;
+    ti.rb = s0 + rbl;
+    ti.lrow0 = (ti.rb - e_rb0) * a.tl.BM;
     ti.row0 = tb.offsets[e] + ti.lrow0;
     ti.nrows = min(a.tl.BM, tb.offsets[e + 1] - ti.row0);
     ti.n0 = ct * BN;
@@ -83,19 +100,50 @@ __device__ __forceinline__ TileInfo decode_tile(const KArgs &a, const Tables &tb
     return ti;
 }
 
+// All global pointers of the argument block that the tile code uses, marked as
+// pointing to global memory (see as_global).
+__device__ __forceinline__ void mark_global(KArgs &a) {
+    a.x = as_global((const char *)a.x);
+    a.W1 = as_global((const char *)a.W1);
+    a.W3 = as_global((const char *)a.W3);
+    a.W2 = as_global((const char *)a.W2);
+    a.h = as_global((char *)a.h);
+    a.perm = as_global(a.perm);
+    a.staging = as_global((char *)a.staging);
+    a.flags = as_global(a.flags);
+    a.slot_flag = as_global(a.slot_flag);
+    a.dest_counter = as_global(a.dest_counter);
+    a.dest_flag_begin = as_global(a.dest_flag_begin);
+    a.h_ready = as_global(a.h_ready);
+    a.offsets = as_global(a.offsets);
+    a.rb_base = as_global(a.rb_base);
+    a.rb_expert = as_global(a.rb_expert);
+    a.ctrl = as_global(a.ctrl);
+}
+
+// The decode tables: the copies a workgroup made in LDS after the plan (see the
+// megakernel), else the workspace arrays.
+__device__ __forceinline__ Tables decode_tables(const KArgs &a, char *smem, int n_rb) {
+    Tables tb;
+    tb.n_rb = n_rb;
+    if (a.tab_lds_off > 0) {
+        tb.offsets = (const int32_t *)(smem + a.tab_lds_off);
+        tb.rb_base = tb.offsets + a.E + 1;
+        tb.rb_expert = tb.rb_base + a.E + 1;
+    } else {
+        tb.offsets = a.offsets;
+        tb.rb_base = a.rb_base;
+        tb.rb_expert = a.rb_expert;
+    }
+    return tb;
+}
+
 // GEMM1 + SwiGLU: h[rows of the block, n0 .. n0+ncols) = silu(x W1[e]) * (x W3[e]).
 // Rows are gathered straight from x through perm: the permuted activations are
 // never materialised.
 template <class P>
-__device__ __attribute__((noinline)) void g1_tile(const KArgs &a_in, const Tables &tb_in, int lt, char *smem) {
+__device__ __forceinline__ void g1_tile(const KArgs &a, const TileInfo &ti, char *smem) {
     using ET = typename P::ET;
-    // private copies: the caller's objects live in memory (this function is not inlined, so
-    // that the GEMM gets a register allocation of its own), and every global store below
-    // would otherwise force their fields to be re-read
-    const KArgs a = a_in;
-    const Tables tb = tb_in;
-    const TileInfo ti = decode_tile(a, tb, lt, a.tl.NT1, P::BN1, a.f);
-    if (!ti.valid) return;
     const ET *x = (const ET *)a.x;
     const int N = a.N;
     auto rowptr = [&](int r) {
@@ -104,7 +152,9 @@ __device__ __attribute__((noinline)) void g1_tile(const KArgs &a_in, const Table
         return x + (size_t)(s / a.k) * a.d;
     };
     const size_t wofs = (size_t)ti.e * a.d * a.f + ti.n0;
+    MOE_TT_BEGIN();
     P::template gemm<true>(rowptr, (const ET *)a.W1 + wofs, (const ET *)a.W3 + wofs, a.f, ti.ncols, a.d, smem);
+    MOE_TT(a.ctrl, 1);
     const int ppr = ti.ncols * (int)sizeof(ET) / 16;
     char *h = (char *)a.h;
     for (int q = threadIdx.x; q < ti.nrows * ppr; q += kThreads) {
@@ -113,11 +163,13 @@ __device__ __attribute__((noinline)) void g1_tile(const KArgs &a_in, const Table
             *(const uint4 *)(smem + r * P::C_STRIDE + c * 16);
     }
     sync_stores();
+    MOE_TT(a.ctrl, 2);
     if (threadIdx.x == 0) {
         fence_release(0);
         atomicAdd(&a.h_ready[ti.rb], 1u);
         atomicAdd(&a.ctrl->stats[4], 1ull);
     }
+    MOE_TT(a.ctrl, 3);
 }
 
 // Publish the y tile sitting in the LDS C tile.  A publish tile is the part of
@@ -139,6 +191,7 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
     int *s_seg = s_dest + P::BM;                 // [BM+1] first local row of publish row-tile i
     int *s_nseg = s_seg + P::BM + 1;
     const int N = a.N;
+    MOE_TT_BEGIN();
     for (int r = tid; r < ti.nrows; r += kThreads) {
         int s = a.perm[ti.row0 + r];
         s = min(max(s, 0), N - 1);
@@ -161,6 +214,7 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
         }
     }
     __syncthreads();
+    MOE_TT(a.ctrl, 11);
     const int nseg = *s_nseg;
     const int cbn = (ti.ncols + a.tile_n - 1) / a.tile_n;  // column blocks in this compute tile
     const int cb0 = ti.n0 / a.tile_n;
@@ -200,6 +254,7 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
     } else {
         copy_rows(0, ti.nrows, 0, ti.ncols * ES / 16);
         sync_stores();
+        MOE_TT(a.ctrl, 12);
         if (wave == 0) {
             fence_release(0);  // the rows of this tile may now be counted
             u64 n_fence = 0, n_flag = 0;
@@ -218,7 +273,9 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
                     const int src = __ffsll((long long)m) - 1;
                     m &= m - 1;
                     const int dd = __shfl(dst, src, 64);
-                    fence_acquire(0);    // every tile counted for dd is visible here
+                    // every tile counted for dd was released (device scope) by its writer before
+                    // it was counted
+                    fence_acquire_no_invalidate();
                     fence_release(sys);  // the one fence of this destination
                     const int f0 = a.dest_flag_begin[dd], f1 = a.dest_flag_begin[dd + 1];
                     for (int fi = f0 + lane; fi < f1; fi += 64) st_relaxed(&a.flags[fi], a.epoch, sys);
@@ -238,22 +295,82 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
         }
     }
     __syncthreads();
+    MOE_TT(a.ctrl, 13);
 }
 
 // GEMM2 + publish: y[rows of the block, n0 .. n0+ncols) = h W2[e], written to
 // staging row perm[p] (the slot that asked for it).  The caller has already
 // waited for the block's h rows.
 template <class P>
-__device__ __attribute__((noinline)) void g2_tile(const KArgs &a_in, const TileInfo &ti_in, char *smem) {
+__device__ __forceinline__ void g2_tile(const KArgs &a, const TileInfo &ti, char *smem) {
     using ET = typename P::ET;
-    const KArgs a = a_in;  // private copies, see g1_tile
-    const TileInfo ti = ti_in;
     const ET *h = (const ET *)a.h;
     auto rowptr = [&](int r) { return h + (size_t)(ti.row0 + min(r, ti.nrows - 1)) * a.f; };
     const ET *B0 = (const ET *)a.W2 + (size_t)ti.e * a.f * a.d + ti.n0;
+    MOE_TT_BEGIN();
     P::template gemm<false>(rowptr, B0, B0, a.d, ti.ncols, a.f, smem);
+    MOE_TT(a.ctrl, 7);
     publish_tile<P>(a, ti, smem);
+    MOE_TT(a.ctrl, 8);
     if (threadIdx.x == 0) atomicAdd(&a.ctrl->stats[5], 1ull);
+}
+
+// ---- the tile stages of the megakernel
+// Each stage function works through the GEMM1 (or GEMM2) entries of one tile
+// queue, starting with entry `i` that the caller has drawn, and returns the
+// first entry it drew that is not its own.  They are real calls, one per queue
+// and kind, so that each GEMM main loop gets a register allocation of its own
+// whatever else the kernel contains; being called once per queue rather than
+// once per tile keeps the cost of a call (saving and restoring registers
+// through scratch memory) out of the tile loop.  The argument block comes in
+// by address (scalar loads), LDS as an offset.
+struct StageLds {  // broadcast slots of the tile loop, in dynamic LDS at KArgs::sched_lds_off
+    int next, ok;
+};
+
+template <class P, bool GATED>
+__device__ __attribute__((noinline)) int tile_stage(KArgsAddr args, u32 smem_off, int q, int n_rb, int i) {
+    KArgs a = load_kernel_args(args);
+    mark_global(a);
+    char *smem = lds_at((u32)uniform((int)smem_off));
+    q = uniform(q), n_rb = uniform(n_rb), i = uniform(i);
+    const int tid = threadIdx.x;
+    Ctrl *c = a.ctrl;
+    StageLds *sl = (StageLds *)(smem + a.sched_lds_off);
+    const Tables tb = decode_tables(a, smem, n_rb);
+    const TileQueue tq = tile_queue(a, n_rb, q);
+    const int first = GATED ? 0 : tq.n1, last = GATED ? tq.n1 : tq.n1 + tq.n2;
+    while (i >= first && i < last) {
+        u32 next = 0;
+        if (tid == 0) next = atomicAdd(&c->tile_next[q], 1u);  // consumed at the end of this tile
+        MOE_TT_BEGIN();
+        if (GATED) {
+            const TileInfo ti = decode_tile(a, tb, tq, i, a.tl.NT1, P::BN1, a.f);
+            MOE_TT(c, 0);
+            g1_tile<P>(a, ti, smem);
+            MOE_TT(c, 4);
+        } else {
+            const TileInfo ti = decode_tile(a, tb, tq, i - tq.n1, a.tl.NT2, P::BN2, a.d);
+            // h rows are written once, by GEMM1 tiles that released them before counting themselves
+            if (tid == 0) sl->ok = wait_ge<false>(c, &a.h_ready[ti.rb], (u32)a.tl.NT1) ? 1 : 0;
+            __syncthreads();
+            MOE_TT(c, 5);
+            if (sl->ok) g2_tile<P>(a, ti, smem);
+            MOE_TT(c, 9);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            mark_phase_end(c, GATED ? 3 : 4);
+            sl->next = (int)next;
+        }
+        __syncthreads();
+        i = uniform(sl->next);
+        MOE_TT(c, 10);
+#ifdef MOE_TILE_TIMING
+        if (tid == 0) atomicMax(&c->dbg[(GATED ? 16 : 24) + q], now_ticks() - c->t0);
+#endif
+    }
+    return i;
 }
 
 // ---- combine

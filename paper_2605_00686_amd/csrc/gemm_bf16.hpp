@@ -55,7 +55,8 @@ struct TileCfg {
     static_assert((NS - 1) * LPS <= 63, "vmcnt range");
 };
 
-__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + __expf(-g)) * u; }
+// silu(g) * u; the hardware reciprocal (1 ulp) is far inside the bf16 rounding of the result
+__device__ __forceinline__ float silu_mul(float g, float u) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u; }
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {

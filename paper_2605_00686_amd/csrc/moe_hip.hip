@@ -54,14 +54,20 @@ __global__ __launch_bounds__(kThreads) void k_combine(KArgs a) {
     combine_task<ET, false>(a, blockIdx.x);
 }
 
-// The whole layer in one persistent kernel.  Workgroups draw task numbers from
-// one counter; the task list is ordered so that a task only ever waits for
-// lower-numbered tasks, all of which have been drawn by workgroups that are
-// already running: no wait can deadlock, whatever the grid size.  (A workgroup
-// draws its next task while it works on the current one, which hides the
-// counter's latency and keeps the argument intact: the task in hand only waits
-// for lower-numbered ones.)
-//   [gate tasks | plan | permutation blocks | GEMM1 tiles | GEMM2 tiles | combine tasks]
+// The whole layer in one persistent kernel.  Every workgroup walks through three
+// stages, drawing work from counters in the control block:
+//   1. front tasks, one counter, in this order: [gate tasks | plan | permutation blocks];
+//   2. GEMM tiles, one queue per XCD (see TileQueue): its own XCD's queue first, then the
+//      others, each queue listing its GEMM1 tiles before its GEMM2 tiles;
+//   3. combine tasks, one counter.
+// No wait can deadlock, whatever the grid size: a task only waits for tasks of an
+// earlier kind (permutation <- plan <- gate, GEMM1 <- permutation, GEMM2 <- GEMM1 tiles
+// earlier in the same queue, combine <- GEMM2), a workgroup only moves to a later stage
+// or to another queue when every entry before has been drawn, and whoever drew an entry
+// is running it.  So the not yet finished entry of the earliest kind is always either
+// running with everything it needs, or about to be drawn by a workgroup that is not
+// waiting.  A workgroup draws its next entry while it works on the current one, which
+// hides the counter's latency.
 template <class P>
 __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) {
     using ET = typename P::ET;
@@ -69,6 +75,7 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
     __shared__ int s_task, s_ok, s_last;
     Ctrl *c = a.ctrl;
     const int tid = threadIdx.x;
+    const KArgsAddr kargs = kernel_args_address();
     if (tid == 0) {
         atomicCAS(&c->t0, 0ull, now_ticks());
         atomicAdd(&c->stats[15], 1ull);
@@ -118,10 +125,28 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
         bad = bad || !s_ok;
         __syncthreads();
     };
+    // thread 0 draws the next entry of `counter` at the start of a task (next = ...) and
+    // hands it to the workgroup at the end
+    auto finish_task = [&](int phase, u32 next) {
+        __syncthreads();
+        if (tid == 0) {
+            mark_phase_end(c, phase);
+            s_task = (int)next;
+        }
+        __syncthreads();
+        return s_task;
+    };
+    auto draw_first = [&](u32 *counter) {
+        __syncthreads();
+        if (tid == 0) s_task = (int)atomicAdd(counter, 1u);
+        __syncthreads();
+        return s_task;
+    };
 
-    while (task < a.t_end) {
+    // ---- stage 1: gate, plan, permutation
+    while (task < a.t_g1) {
         u32 next = 0;
-        if (tid == 0) next = atomicAdd(&c->next_task, 1u);  // consumed at the end of this task
+        if (tid == 0) next = atomicAdd(&c->next_task, 1u);
         int phase;
         if (task < a.t_plan) {
             phase = 0;
@@ -141,7 +166,7 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
                 fence_release(0);
                 __hip_atomic_store(&c->plan_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-        } else if (task < a.t_g1) {
+        } else {
             phase = 2;
             need_plan();
             if (!bad) perm_task<ET>(a, task - a.t_perm, smem);
@@ -150,43 +175,39 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
                 fence_release(0);
                 atomicAdd(&c->perm_done, 1u);
             }
-        } else if (task < a.t_g2) {
-            phase = 3;
-            need_perm();
-            if (!bad) {
-                // the tile functions are real calls: hand them copies, so that the kernel's own
-                // argument block and tables never have their address taken and stay in registers
-                const KArgs ac = a;
-                const Tables tc = tb;
-                g1_tile<P>(ac, tc, task - a.t_g1, smem);
-            }
-        } else if (task < a.t_comb) {
-            phase = 4;
-            need_plan();
-            TileInfo ti;
-            ti.valid = false;
-            if (!bad) ti = decode_tile(a, tb, task - a.t_g2, a.tl.NT2, P::BN2, a.d);
-            if (ti.valid) {  // uniform: every thread decodes the same tile
-                if (tid == 0) s_ok = wait_ge(c, &a.h_ready[ti.rb], (u32)a.tl.NT1) ? 1 : 0;
-                __syncthreads();
-                if (s_ok) {
-                    const KArgs ac = a;
-                    const TileInfo tic = ti;
-                    g2_tile<P>(ac, tic, smem);
-                }
-            }
-        } else {
-            phase = 5;
-            need_perm();
-            if (!bad) combine_task<ET, true>(a, task - a.t_comb);
         }
-        __syncthreads();
+        task = finish_task(phase, next);
+    }
+
+    // ---- stage 2: GEMM tiles, this XCD's queue first
+    need_perm();
+    if (!bad) {
+        const int home = xcd_id() % kTileQueues;
+        for (int s = 0; s < kTileQueues; ++s) {
+            const int q = (home + s) % kTileQueues;
+            const TileQueue tq = tile_queue(a, tb.n_rb, q);
+            const int n_entries = tq.n1 + tq.n2;
+            if (n_entries == 0) continue;
+            int i = draw_first(&c->tile_next[q]);
+            if (i < tq.n1) i = tile_stage<P, true>(kargs, lds_offset(smem), q, tb.n_rb, i);
+            if (i < n_entries) i = tile_stage<P, false>(kargs, lds_offset(smem), q, tb.n_rb, i);
+        }
+
+#ifdef MOE_TILE_TIMING
         if (tid == 0) {
-            mark_phase_end(c, phase);
-            s_task = (int)next;
+            const u64 t = now_ticks() - c->t0;
+            atomicAdd(&c->dbg[14], t);
+            atomicMax(&c->dbg[15], t);
         }
-        __syncthreads();
-        task = s_task;
+#endif
+        // ---- stage 3: combine
+        int ct = draw_first(&c->comb_next);
+        while (ct < a.nCT) {
+            u32 next = 0;
+            if (tid == 0) next = atomicAdd(&c->comb_next, 1u);
+            combine_task<ET, true>(a, ct);
+            ct = finish_task(5, next);
+        }
     }
     // last workgroup out copies the statistics and clears the control block
     sync_stores();
@@ -207,6 +228,22 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
             }
         }
         __syncthreads();
+#ifdef MOE_TILE_TIMING
+        if (tid == 0) {
+            const double n1 = (double)c->stats[4], n2 = (double)c->stats[5];
+            printf("tile timing (us/tile): g1 n=%.0f pre %.2f call %.2f [gemm %.2f store %.2f release %.2f] | g2 n=%.0f wait %.2f call %.2f "
+                   "[gemm %.2f publish %.2f (rows %.2f copy %.2f signal %.2f)] | finish %.2f\n",
+                   n1, c->dbg[0] / n1 / 100., c->dbg[4] / n1 / 100., c->dbg[1] / n1 / 100., c->dbg[2] / n1 / 100., c->dbg[3] / n1 / 100., n2,
+                   c->dbg[5] / n2 / 100., c->dbg[9] / n2 / 100., c->dbg[7] / n2 / 100., c->dbg[8] / n2 / 100., c->dbg[11] / n2 / 100.,
+                   c->dbg[12] / n2 / 100., c->dbg[13] / n2 / 100., c->dbg[10] / (n1 + n2) / 100.);
+            printf("tiles done (us): avg over workgroups %.1f, last %.1f; per queue g1 end", c->dbg[14] / (double)gridDim.x / 100., c->dbg[15] / 100.);
+            for (int q = 0; q < 8; ++q) printf(" %.0f", c->dbg[16 + q] / 100.);
+            printf("; g2 end");
+            for (int q = 0; q < 8; ++q) printf(" %.0f", c->dbg[24 + q] / 100.);
+            printf("\n");
+        }
+        __syncthreads();
+#endif
         u32 *z = (u32 *)c;
         for (size_t i = tid; i < a.zero_bytes / 4; i += kThreads) z[i] = 0u;
     }
@@ -317,9 +354,7 @@ static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
     a->t_plan = pl.nRT;
     a->t_perm = a->t_plan + 1;
     a->t_g1 = a->t_perm + pl.nPB;
-    a->t_g2 = a->t_g1 + pl.tl.maxRB * pl.tl.NT1;
-    a->t_comb = a->t_g2 + pl.tl.maxRB * pl.tl.NT2;
-    a->t_end = a->t_comb + pl.nCT;
+    a->t_end = a->t_g1 + pl.tl.maxRB * (pl.tl.NT1 + pl.tl.NT2) + pl.nCT;
     char *ws = (char *)workspace;
     if (ws) {
         a->ctrl = (Ctrl *)(ws + pl.o_ctrl);
@@ -364,10 +399,12 @@ static int launch_mega(const Plan &pl, const KArgs &a_in, hipStream_t st) {
     KArgs a = a_in;
     const size_t tab_bytes = (size_t)(2 * (pl.p.E + 1) + pl.tl.maxRB) * 4;
     a.tab_lds_off = 0;
-    if (tab_bytes <= 8 * 1024) {
+    if (tab_bytes <= 6 * 1024) {  // small enough that two workgroups of the 128-row tile still share a CU
         a.tab_lds_off = (int)align_up(smem, 16);
         smem = a.tab_lds_off + tab_bytes;
     }
+    a.sched_lds_off = (int)align_up(smem, 16);
+    smem = a.sched_lds_off + 16;
     auto kern = k_megakernel<P>;
     int rc = set_smem(kern, smem);
     if (rc) return rc;
