@@ -36,7 +36,7 @@ struct Ctrl {
     u64 t0;          // wall-clock tick of the first task drawn
     u64 stats[MOE_NUM_STATS];
 #ifdef MOE_TILE_TIMING
-    u64 dbg[32];  // development build only: time spent in the parts of a tile, summed over tiles
+    u64 dbg[40];  // development build only: time spent in the parts of a tile, summed over tiles
 #endif
 };
 

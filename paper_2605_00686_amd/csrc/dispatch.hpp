@@ -24,7 +24,7 @@ __host__ __device__ inline size_t plan_smem_bytes(int E, int R, int nPB) {
 // rb_base, rb_expert, ctrl->n_rb, ctrl->n_flags.  The inputs are first copied
 // to LDS with coalesced loads so that the serial scans below never wait on a
 // global load.
-__device__ void plan_task(const KArgs &a, char *smem) {
+__device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
     const int tid = threadIdx.x;
     const int E = a.E, R = a.R, nPB = a.nPB;
     int32_t *s_cnt = (int32_t *)smem;  // [E]
@@ -140,7 +140,7 @@ __device__ void plan_task(const KArgs &a, char *smem) {
 // number of earlier tokens of the block that chose e: a popcount on a 64-bit
 // per-expert mask.  Deterministic, no arrival-order atomics.
 template <typename ET>
-__device__ void perm_task(const KArgs &a, int b, char *smem) {
+__device__ __forceinline__ void perm_task(const KArgs &a, int b, char *smem) {
     const int tid = threadIdx.x;
     const int E = a.E, k = a.k;
     u64 *mask = (u64 *)smem;  // [E]

@@ -15,7 +15,8 @@ struct Bf16Policy {
     static constexpr int BM = C::BM, BN1 = C::BN / 2, BN2 = C::BN;
     static constexpr int C_STRIDE = C::C_STRIDE;
     static constexpr int SMEM_MAIN = C::SMEM_MAIN;
-    static constexpr int MIN_WAVES = (C::BM <= 128) ? 2 : 1;  // wavefronts per SIMD the kernel is built for
+    // wavefronts per SIMD the kernel is built for: two workgroups per CU where their LDS fits
+    static constexpr int MIN_WAVES = (2 * (C::SMEM_MAIN + 8 * 1024) <= 160 * 1024) ? 2 : 1;
     template <bool GATED, class RowPtr>
     static __device__ __forceinline__ void gemm(RowPtr rp, const ET *B0, const ET *B1, int ldb, int ncols, int K,
                                                 char *smem) {
@@ -42,7 +43,7 @@ constexpr int tile_smem_bytes() {
 
 // stage depth / count per shape: the best of the variants measured on MI355X
 using CfgL = TileCfg<4, 4, 2, 2, 32, 4>;  // 256 x 256, wavefront 128 x 128
-using CfgM = TileCfg<2, 4, 2, 2, 32, 3>;  // 128 x 256, wavefront  64 x 128, two workgroups per CU
+using CfgM = TileCfg<2, 4, 2, 2, 64, 3>;  // 128 x 256, wavefront  64 x 128
 using CfgS = TileCfg<1, 2, 1, 4, 64, 2>;  //  32 x 256, wavefront  32 x  64, two workgroups per CU
 
 struct TileInfo {
@@ -100,25 +101,37 @@ __device__ __forceinline__ TileInfo decode_tile(const KArgs &a, const Tables &tb
     return ti;
 }
 
-// All global pointers of the argument block that the tile code uses, marked as
-// pointing to global memory (see as_global).
+// Every pointer of the argument block, marked as pointing to global memory
+// (see as_global).
 __device__ __forceinline__ void mark_global(KArgs &a) {
     a.x = as_global((const char *)a.x);
+    a.Wg = as_global((const char *)a.Wg);
+    a.bias = as_global(a.bias);
     a.W1 = as_global((const char *)a.W1);
     a.W3 = as_global((const char *)a.W3);
     a.W2 = as_global((const char *)a.W2);
-    a.h = as_global((char *)a.h);
+    a.idx = as_global(a.idx);
+    a.w = as_global(a.w);
+    a.counts = as_global(a.counts);
+    a.offsets = as_global(a.offsets);
     a.perm = as_global(a.perm);
+    a.inv_perm = as_global(a.inv_perm);
+    a.slot_flag = as_global(a.slot_flag);
     a.staging = as_global((char *)a.staging);
     a.flags = as_global(a.flags);
-    a.slot_flag = as_global(a.slot_flag);
-    a.dest_counter = as_global(a.dest_counter);
+    a.out = as_global((char *)a.out);
+    a.ctrl = as_global(a.ctrl);
+    a.blk_hist = as_global(a.blk_hist);
+    a.blk_base = as_global(a.blk_base);
+    a.seg_cnt = as_global(a.seg_cnt);
+    a.seg_begin = as_global(a.seg_begin);
+    a.flag_base = as_global(a.flag_base);
     a.dest_flag_begin = as_global(a.dest_flag_begin);
-    a.h_ready = as_global(a.h_ready);
-    a.offsets = as_global(a.offsets);
+    a.dest_counter = as_global(a.dest_counter);
     a.rb_base = as_global(a.rb_base);
     a.rb_expert = as_global(a.rb_expert);
-    a.ctrl = as_global(a.ctrl);
+    a.h_ready = as_global(a.h_ready);
+    a.h = as_global((char *)a.h);
 }
 
 // The decode tables: the copies a workgroup made in LDS after the plan (see the
@@ -141,8 +154,10 @@ __device__ __forceinline__ Tables decode_tables(const KArgs &a, char *smem, int 
 // GEMM1 + SwiGLU: h[rows of the block, n0 .. n0+ncols) = silu(x W1[e]) * (x W3[e]).
 // Rows are gathered straight from x through perm: the permuted activations are
 // never materialised.
-template <class P>
-__device__ __forceinline__ void g1_tile(const KArgs &a, const TileInfo &ti, char *smem) {
+// `after_gemm()` runs between the main loop and the write-out (the megakernel draws
+// its next tile there, so that the counter's latency hides behind the write-out).
+template <class P, class Hook>
+__device__ __forceinline__ void g1_tile(const KArgs &a, const TileInfo &ti, char *smem, Hook after_gemm) {
     using ET = typename P::ET;
     const ET *x = (const ET *)a.x;
     const int N = a.N;
@@ -154,6 +169,7 @@ __device__ __forceinline__ void g1_tile(const KArgs &a, const TileInfo &ti, char
     const size_t wofs = (size_t)ti.e * a.d * a.f + ti.n0;
     MOE_TT_BEGIN();
     P::template gemm<true>(rowptr, (const ET *)a.W1 + wofs, (const ET *)a.W3 + wofs, a.f, ti.ncols, a.d, smem);
+    after_gemm();
     MOE_TT(a.ctrl, 1);
     const int ppr = ti.ncols * (int)sizeof(ET) / 16;
     char *h = (char *)a.h;
@@ -301,32 +317,38 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
 // GEMM2 + publish: y[rows of the block, n0 .. n0+ncols) = h W2[e], written to
 // staging row perm[p] (the slot that asked for it).  The caller has already
 // waited for the block's h rows.
-template <class P>
-__device__ __forceinline__ void g2_tile(const KArgs &a, const TileInfo &ti, char *smem) {
+template <class P, class Hook>
+__device__ __forceinline__ void g2_tile(const KArgs &a, const TileInfo &ti, char *smem, Hook after_gemm) {
     using ET = typename P::ET;
     const ET *h = (const ET *)a.h;
     auto rowptr = [&](int r) { return h + (size_t)(ti.row0 + min(r, ti.nrows - 1)) * a.f; };
     const ET *B0 = (const ET *)a.W2 + (size_t)ti.e * a.f * a.d + ti.n0;
     MOE_TT_BEGIN();
     P::template gemm<false>(rowptr, B0, B0, a.d, ti.ncols, a.f, smem);
+    after_gemm();
     MOE_TT(a.ctrl, 7);
     publish_tile<P>(a, ti, smem);
     MOE_TT(a.ctrl, 8);
     if (threadIdx.x == 0) atomicAdd(&a.ctrl->stats[5], 1ull);
 }
 
-// ---- the tile stages of the megakernel
-// Each stage function works through the GEMM1 (or GEMM2) entries of one tile
-// queue, starting with entry `i` that the caller has drawn, and returns the
-// first entry it drew that is not its own.  They are real calls, one per queue
-// and kind, so that each GEMM main loop gets a register allocation of its own
-// whatever else the kernel contains; being called once per queue rather than
-// once per tile keeps the cost of a call (saving and restoring registers
-// through scratch memory) out of the tile loop.  The argument block comes in
-// by address (scalar loads), LDS as an offset.
-struct StageLds {  // broadcast slots of the tile loop, in dynamic LDS at KArgs::sched_lds_off
+// ---- the stages of the megakernel
+// The megakernel is a sequence of stages, each of which draws work from a
+// counter of the control block until there is none left for it.  The two GEMM
+// stages are real calls (not inlined), so that each GEMM main loop gets a
+// register allocation of its own whatever else the kernel contains; a stage
+// loops over its tiles inside the call, which keeps the cost of a call (saving
+// and restoring registers through scratch memory) out of the tile loop.  They
+// take the argument block by address and read it with scalar loads (a
+// reference to the kernel's own copy would force that copy into per-lane
+// scratch memory, for every stage), and LDS as an offset.  Everything else is
+// inlined into the kernel, so that the kernel's launch bounds govern it.
+struct StageLds {  // broadcast slots of a stage's task loop, in dynamic LDS at KArgs::sched_lds_off
     int next, ok;
 };
+
+// GEMM1 (GATED) or GEMM2 entries of tile queue q, starting with entry `i` that
+// the caller has drawn; returns the first entry drawn that is not its own.
 
 template <class P, bool GATED>
 __device__ __attribute__((noinline)) int tile_stage(KArgsAddr args, u32 smem_off, int q, int n_rb, int i) {
@@ -341,13 +363,16 @@ __device__ __attribute__((noinline)) int tile_stage(KArgsAddr args, u32 smem_off
     const TileQueue tq = tile_queue(a, n_rb, q);
     const int first = GATED ? 0 : tq.n1, last = GATED ? tq.n1 : tq.n1 + tq.n2;
     while (i >= first && i < last) {
-        u32 next = 0;
-        if (tid == 0) next = atomicAdd(&c->tile_next[q], 1u);  // consumed at the end of this tile
+        // the next entry is drawn after this tile's main loop and consumed at the end of the tile
+        u32 next = 0x7fffffffu;
+        auto draw = [&]() {
+            if (tid == 0) next = atomicAdd(&c->tile_next[q], 1u);
+        };
         MOE_TT_BEGIN();
         if (GATED) {
             const TileInfo ti = decode_tile(a, tb, tq, i, a.tl.NT1, P::BN1, a.f);
             MOE_TT(c, 0);
-            g1_tile<P>(a, ti, smem);
+            g1_tile<P>(a, ti, smem, draw);
             MOE_TT(c, 4);
         } else {
             const TileInfo ti = decode_tile(a, tb, tq, i - tq.n1, a.tl.NT2, P::BN2, a.d);
@@ -355,7 +380,10 @@ __device__ __attribute__((noinline)) int tile_stage(KArgsAddr args, u32 smem_off
             if (tid == 0) sl->ok = wait_ge<false>(c, &a.h_ready[ti.rb], (u32)a.tl.NT1) ? 1 : 0;
             __syncthreads();
             MOE_TT(c, 5);
-            if (sl->ok) g2_tile<P>(a, ti, smem);
+            if (sl->ok)
+                g2_tile<P>(a, ti, smem, draw);
+            else
+                draw();
             MOE_TT(c, 9);
         }
         __syncthreads();
@@ -419,7 +447,7 @@ struct Vec16<float> {
 // was not ready) followed by one acquire fence at the requested scope.  Then
 // one wavefront per token, 16-byte pieces, up to eight rows in flight per lane.
 template <typename ET, bool WAIT>
-__device__ void combine_task(const KArgs &a, int task) {
+__device__ __forceinline__ void combine_task(const KArgs &a, int task) {
     using V = Vec16<ET>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int k = a.k, sys = a.fence_scope;
@@ -506,6 +534,31 @@ __device__ void combine_task(const KArgs &a, int task) {
             }
             V::store((char *)a.out + (size_t)t * rstride + (size_t)c * 16, acc);
         }
+    }
+}
+
+// Combine tasks from their counter until none is left.  (Inlined into the
+// kernel: only the GEMM stages need a register allocation of their own.)
+template <typename ET>
+__device__ __forceinline__ void combine_stage(const KArgs &a, char *smem) {
+    const int tid = threadIdx.x;
+    Ctrl *c = a.ctrl;
+    StageLds *sl = (StageLds *)(smem + a.sched_lds_off);
+    __syncthreads();
+    if (tid == 0) sl->next = (int)atomicAdd(&c->comb_next, 1u);
+    __syncthreads();
+    int t = uniform(sl->next);
+    while (t < a.nCT) {
+        u32 next = 0;
+        if (tid == 0) next = atomicAdd(&c->comb_next, 1u);
+        combine_task<ET, true>(a, t);
+        __syncthreads();
+        if (tid == 0) {
+            mark_phase_end(c, 5);
+            sl->next = (int)next;
+        }
+        __syncthreads();
+        t = uniform(sl->next);
     }
 }
 

@@ -54,6 +54,67 @@ __global__ __launch_bounds__(kThreads) void k_combine(KArgs a) {
     combine_task<ET, false>(a, blockIdx.x);
 }
 
+// Front tasks of the megakernel from their counter, in this order:
+// [gate tasks | plan | permutation blocks].  Returns nonzero if a wait failed or
+// the routing was found invalid.
+template <typename ET>
+__device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
+    const int tid = threadIdx.x;
+    Ctrl *c = a.ctrl;
+    StageLds *sl = (StageLds *)(smem + a.sched_lds_off);
+    __syncthreads();
+    if (tid == 0) sl->next = (int)atomicAdd(&c->next_task, 1u);
+    __syncthreads();
+    int task = uniform(sl->next);
+    bool seen_plan = false, bad = false;
+    // (the next task is only drawn when this one is done: there are about as many gate tasks
+    // as workgroups, and drawing ahead would give the first workgroups two each)
+    while (task < a.t_g1) {
+        int phase;
+        if (task < a.t_plan) {
+            phase = 0;
+            route_task<ET>(a, task, smem, true);
+            sync_stores();
+            if (tid == 0) {
+                fence_release(0);
+                atomicAdd(&c->route_done, 1u);
+            }
+        } else if (task < a.t_perm) {
+            phase = 1;
+            if (tid == 0) sl->ok = wait_ge(c, &c->route_done, (u32)a.nRT) ? 1 : 0;
+            __syncthreads();
+            if (sl->ok) plan_task(a, smem);
+            sync_stores();
+            if (tid == 0) {
+                fence_release(0);
+                __hip_atomic_store(&c->plan_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        } else {
+            phase = 2;
+            if (!seen_plan) {
+                if (tid == 0) sl->ok = (wait_ge(c, &c->plan_done, 1u) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
+                __syncthreads();
+                seen_plan = true;
+                bad = bad || !sl->ok;
+            }
+            if (!bad) perm_task<ET>(a, task - a.t_perm, smem);
+            sync_stores();
+            if (tid == 0) {
+                fence_release(0);
+                atomicAdd(&c->perm_done, 1u);
+            }
+        }
+        __syncthreads();
+        if (tid == 0) {
+            mark_phase_end(c, phase);
+            sl->next = (int)atomicAdd(&c->next_task, 1u);
+        }
+        __syncthreads();
+        task = uniform(sl->next);
+    }
+    return bad ? 1 : 0;
+}
+
 // The whole layer in one persistent kernel.  Every workgroup walks through three
 // stages, drawing work from counters in the control block:
 //   1. front tasks, one counter, in this order: [gate tasks | plan | permutation blocks];
@@ -67,7 +128,9 @@ __global__ __launch_bounds__(kThreads) void k_combine(KArgs a) {
 // is running it.  So the not yet finished entry of the earliest kind is always either
 // running with everything it needs, or about to be drawn by a workgroup that is not
 // waiting.  A workgroup draws its next entry while it works on the current one, which
-// hides the counter's latency.
+// hides the counter's latency.  The kernel body itself only strings the stage
+// functions together (see StageLds) and never hands out a reference to its argument
+// block.
 template <class P>
 __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) {
     using ET = typename P::ET;
@@ -79,120 +142,50 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
     if (tid == 0) {
         atomicCAS(&c->t0, 0ull, now_ticks());
         atomicAdd(&c->stats[15], 1ull);
-        s_task = (int)atomicAdd(&c->next_task, 1u);
     }
-    __syncthreads();
-    int task = s_task;
-    // what this workgroup has already observed (uniform across its threads)
-    bool seen_plan = false, seen_perm = false, bad = false;
-    Tables tb;
-    tb.offsets = a.offsets;
-    tb.rb_base = a.rb_base;
-    tb.rb_expert = a.rb_expert;
-    tb.n_rb = 0;
-
-    // wait once for the plan (and with it for every gate task); copy the decode tables to LDS
-    auto need_plan = [&]() {
-        if (seen_plan) return;
-        if (tid == 0) s_ok = (wait_ge(c, &c->plan_done, 1u) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
-        __syncthreads();
-        seen_plan = true;
-        bad = bad || !s_ok;
-        if (!bad) {
-            tb.n_rb = (int)c->n_rb;
-            if (a.tab_lds_off > 0) {
-                int32_t *t_off = (int32_t *)(smem + a.tab_lds_off);
-                int32_t *t_rbb = t_off + a.E + 1;
-                int32_t *t_rbe = t_rbb + a.E + 1;
-                for (int i = tid; i <= a.E; i += kThreads) {
-                    t_off[i] = a.offsets[i];
-                    t_rbb[i] = a.rb_base[i];
-                }
-                for (int i = tid; i < tb.n_rb; i += kThreads) t_rbe[i] = a.rb_expert[i];
-                tb.offsets = t_off;
-                tb.rb_base = t_rbb;
-                tb.rb_expert = t_rbe;
-            }
-        }
-        __syncthreads();
-    };
-    auto need_perm = [&]() {
-        need_plan();
-        if (seen_perm) return;
-        if (tid == 0) s_ok = wait_ge(c, &c->perm_done, (u32)a.nPB) ? 1 : 0;
-        __syncthreads();
-        seen_perm = true;
-        bad = bad || !s_ok;
-        __syncthreads();
-    };
-    // thread 0 draws the next entry of `counter` at the start of a task (next = ...) and
-    // hands it to the workgroup at the end
-    auto finish_task = [&](int phase, u32 next) {
-        __syncthreads();
-        if (tid == 0) {
-            mark_phase_end(c, phase);
-            s_task = (int)next;
-        }
-        __syncthreads();
-        return s_task;
-    };
-    auto draw_first = [&](u32 *counter) {
-        __syncthreads();
-        if (tid == 0) s_task = (int)atomicAdd(counter, 1u);
-        __syncthreads();
-        return s_task;
-    };
 
     // ---- stage 1: gate, plan, permutation
-    while (task < a.t_g1) {
-        u32 next = 0;
-        if (tid == 0) next = atomicAdd(&c->next_task, 1u);
-        int phase;
-        if (task < a.t_plan) {
-            phase = 0;
-            route_task<ET>(a, task, smem, true);
-            sync_stores();
-            if (tid == 0) {
-                fence_release(0);
-                atomicAdd(&c->route_done, 1u);
-            }
-        } else if (task < a.t_perm) {
-            phase = 1;
-            if (tid == 0) s_ok = wait_ge(c, &c->route_done, (u32)a.nRT) ? 1 : 0;
-            __syncthreads();
-            if (s_ok) plan_task(a, smem);
-            sync_stores();
-            if (tid == 0) {
-                fence_release(0);
-                __hip_atomic_store(&c->plan_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        } else {
-            phase = 2;
-            need_plan();
-            if (!bad) perm_task<ET>(a, task - a.t_perm, smem);
-            sync_stores();
-            if (tid == 0) {
-                fence_release(0);
-                atomicAdd(&c->perm_done, 1u);
-            }
-        }
-        task = finish_task(phase, next);
-    }
+    bool bad = front_stage<ET>(a, smem) != 0;
 
-    // ---- stage 2: GEMM tiles, this XCD's queue first
-    need_perm();
+    // ---- wait for the plan and the permutation (and with them for every gate task); copy
+    // the decode tables to LDS
+    if (tid == 0) s_ok = (wait_ge(c, &c->plan_done, 1u) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
+    __syncthreads();
+    bad = bad || !s_ok;
+    int n_rb = 0;
     if (!bad) {
+        n_rb = (int)c->n_rb;
+        if (a.tab_lds_off > 0) {
+            int32_t *t_off = (int32_t *)(smem + a.tab_lds_off);
+            int32_t *t_rbb = t_off + a.E + 1;
+            int32_t *t_rbe = t_rbb + a.E + 1;
+            for (int i = tid; i <= a.E; i += kThreads) {
+                t_off[i] = a.offsets[i];
+                t_rbb[i] = a.rb_base[i];
+            }
+            for (int i = tid; i < n_rb; i += kThreads) t_rbe[i] = a.rb_expert[i];
+        }
+    }
+    __syncthreads();
+    if (tid == 0) s_ok = wait_ge(c, &c->perm_done, (u32)a.nPB) ? 1 : 0;
+    __syncthreads();
+    bad = bad || !s_ok;
+
+    if (!bad) {
+        // ---- stage 2: GEMM tiles, this XCD's queue first
         const int home = xcd_id() % kTileQueues;
         for (int s = 0; s < kTileQueues; ++s) {
             const int q = (home + s) % kTileQueues;
-            const TileQueue tq = tile_queue(a, tb.n_rb, q);
+            const TileQueue tq = tile_queue(a, n_rb, q);
             const int n_entries = tq.n1 + tq.n2;
             if (n_entries == 0) continue;
-            int i = draw_first(&c->tile_next[q]);
-            if (i < tq.n1) i = tile_stage<P, true>(kargs, lds_offset(smem), q, tb.n_rb, i);
-            if (i < n_entries) i = tile_stage<P, false>(kargs, lds_offset(smem), q, tb.n_rb, i);
+            __syncthreads();
+            if (tid == 0) s_task = (int)atomicAdd(&c->tile_next[q], 1u);
+            __syncthreads();
+            int i = s_task;
+            if (i < tq.n1) i = tile_stage<P, true>(kargs, lds_offset(smem), q, n_rb, i);
+            if (i < n_entries) i = tile_stage<P, false>(kargs, lds_offset(smem), q, n_rb, i);
         }
-
 #ifdef MOE_TILE_TIMING
         if (tid == 0) {
             const u64 t = now_ticks() - c->t0;
@@ -201,13 +194,7 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
         }
 #endif
         // ---- stage 3: combine
-        int ct = draw_first(&c->comb_next);
-        while (ct < a.nCT) {
-            u32 next = 0;
-            if (tid == 0) next = atomicAdd(&c->comb_next, 1u);
-            combine_task<ET, true>(a, ct);
-            ct = finish_task(5, next);
-        }
+        combine_stage<ET>(a, smem);
     }
     // last workgroup out copies the statistics and clears the control block
     sync_stores();
@@ -236,6 +223,8 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
                    n1, c->dbg[0] / n1 / 100., c->dbg[4] / n1 / 100., c->dbg[1] / n1 / 100., c->dbg[2] / n1 / 100., c->dbg[3] / n1 / 100., n2,
                    c->dbg[5] / n2 / 100., c->dbg[9] / n2 / 100., c->dbg[7] / n2 / 100., c->dbg[8] / n2 / 100., c->dbg[11] / n2 / 100.,
                    c->dbg[12] / n2 / 100., c->dbg[13] / n2 / 100., c->dbg[10] / (n1 + n2) / 100.);
+            printf("gate (us/task, thread 0): logits %.2f, top-k and histograms %.2f\n", c->dbg[32] / (double)a.nRT / 100.,
+                   c->dbg[33] / (double)a.nRT / 100.);
             printf("tiles done (us): avg over workgroups %.1f, last %.1f; per queue g1 end", c->dbg[14] / (double)gridDim.x / 100., c->dbg[15] / 100.);
             for (int q = 0; q < 8; ++q) printf(" %.0f", c->dbg[16 + q] / 100.);
             printf("; g2 end");
@@ -393,7 +382,8 @@ static int set_smem(K kernel, size_t bytes) {
 template <class P>
 static int launch_mega(const Plan &pl, const KArgs &a_in, hipStream_t st) {
     size_t smem = tile_smem_bytes<P>();
-    if (a_in.Wg && route_smem_bytes(pl.p.E) > smem) smem = route_smem_bytes(pl.p.E);
+    const size_t rsm = route_smem_bytes(pl.p.E, elem_size(pl.p.dtype));
+    if (a_in.Wg && rsm > smem) smem = rsm;
     if (plan_smem(pl) > smem) smem = plan_smem(pl);
     // decode tables live behind everything else, for the life of the workgroup
     KArgs a = a_in;
@@ -471,7 +461,7 @@ int moe_route(const moe_problem_t *p, const void *x, const void *Wg, const float
     KArgs a;
     fill_args(pl, nullptr, &a);
     a.x = x; a.Wg = Wg; a.bias = gate_bias; a.idx = topk_idx; a.w = topk_w;
-    const size_t smem = route_smem_bytes(p->E);
+    const size_t smem = route_smem_bytes(p->E, elem_size(p->dtype));
     hipStream_t st = (hipStream_t)stream;
     if (p->dtype == MOE_DT_F32) {
         if ((rc = set_smem(k_route<float>, smem))) return rc;

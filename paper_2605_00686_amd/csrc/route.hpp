@@ -7,9 +7,42 @@
 namespace moe {
 
 typedef __attribute__((ext_vector_type(4))) double f64x4_t;
+typedef __attribute__((ext_vector_type(4))) u32 u32x4_t;  // 16 bytes in registers
 
-__host__ __device__ inline size_t route_smem_bytes(int E) {
-    return (size_t)kRouteTokens * E * 8;  // logits [16][E] f64
+// How a gate task lays out its work.  The gate weights and the task's 16 rows
+// of x pass through LDS in chunks of KC reduction indices (weights: row stride
+// RS bytes, x: row stride XRS bytes, both padded so that the rows a wavefront
+// reads at once fall into different banks); the E/16 expert blocks are dealt to
+// `groups` groups of wavefronts, and the `parts` wavefronts of a group take
+// alternate 16-index pieces of every chunk.
+struct RouteShape {
+    int RS, XRS, KC, nb, groups, parts, nbw;
+};
+__host__ __device__ inline int route_pad_row(int bytes, int target_dw) {
+    const int dw = (bytes + 3) / 4;
+    return 4 * (dw + (((target_dw - dw) % 64) + 64) % 64);
+}
+__host__ __device__ inline RouteShape route_shape(int E, int elem_size) {
+    RouteShape r;
+    const int target = (elem_size == 2) ? 8 : 16;  // dwords one 16-lane read covers
+    r.RS = route_pad_row(E * elem_size, target);
+    const int xlim = 8 * 1024 / (kRouteTokens * elem_size);  // x chunk of at most 8 KB
+    r.KC = (16 * 1024 / r.RS) / 16 * 16;                     // weight chunk of about 16 KB
+    if (r.KC > xlim) r.KC = xlim;
+    if (r.KC < 16) r.KC = 16;
+    r.XRS = route_pad_row(r.KC * elem_size, target);
+    r.nb = (E + 15) / 16;
+    r.groups = r.nb >= 4 ? 4 : r.nb >= 2 ? 2 : 1;
+    r.parts = 4 / r.groups;
+    r.nbw = (r.nb + r.groups - 1) / r.groups;
+    return r;
+}
+__host__ __device__ inline size_t route_stage_bytes(const RouteShape &r) {
+    return (size_t)r.KC * r.RS + (size_t)kRouteTokens * r.XRS;
+}
+__host__ __device__ inline size_t route_smem_bytes(int E, int elem_size) {
+    const RouteShape r = route_shape(E, elem_size);
+    return (size_t)kRouteTokens * E * 8 + 2 * route_stage_bytes(r);  // logits [16][E] f64 + two chunks
 }
 
 // (value, index) argmax step: larger value wins, equal values -> lower index
@@ -25,116 +58,152 @@ struct RouteLoad;
 template <>
 struct RouteLoad<bf16_t> {
     typedef uint2 x4_t;  // four consecutive bf16
-    typedef u32 raw_t;   // one bf16 in the low half
     static __device__ __forceinline__ double get(const x4_t &v, int s) {
         const u32 w = (s < 2) ? v.x : v.y;
         return (double)__uint_as_float((s & 1) ? (w & 0xffff0000u) : (w << 16));
     }
-    static __device__ __forceinline__ raw_t load_raw(const bf16_t *p) { return (u32)*p; }
-    static __device__ __forceinline__ double to_double(raw_t r) { return (double)__uint_as_float(r << 16); }
+    // value of the raw element, or 0.0 when keep == 0 (keep is 0 or ~0: no branch around the load)
+    static __device__ __forceinline__ double to_double(bf16_t r, u32 keep) {
+        return (double)__uint_as_float(((u32)r << 16) & keep);
+    }
 };
 template <>
 struct RouteLoad<float> {
     typedef float4 x4_t;
-    typedef float raw_t;
     static __device__ __forceinline__ double get(const x4_t &v, int s) {
         return (double)(s == 0 ? v.x : s == 1 ? v.y : s == 2 ? v.z : v.w);
     }
-    static __device__ __forceinline__ raw_t load_raw(const float *p) { return *p; }
-    static __device__ __forceinline__ double to_double(raw_t r) { return (double)r; }
+    static __device__ __forceinline__ double to_double(float r, u32 keep) {
+        return (double)__uint_as_float(__float_as_uint(r) & keep);
+    }
 };
 
 // Logits of tokens [t0, t0+16) into lg[16][E] (LDS, fp64) with the fp64 matrix
 // cores: D[token][expert] += x[token][k] * Wg[k][expert], 16 x 16 x 4 per
 // instruction.  bf16/fp32 inputs convert exactly and their products are exact
 // in fp64, so the only rounding is the fp64 accumulation.  Lane l feeds token
-// (or expert) l % 16 and reduction index 4*(l / 16) + s within a chunk of 16;
-// the four wavefronts take contiguous quarters of the reduction and add their
-// partial sums into LDS one after the other (fixed order: deterministic).
-// NB expert blocks of 16 starting at block eb0; U chunks of 16 per iteration,
-// the operands of the next iteration are in flight while this one multiplies
-// (U * NB is kept near 8 so that an iteration hides a trip to L2).
-template <typename ET, int NB, int U>
-__device__ void route_logits(const KArgs &a, int t0, int eb0, char *smem) {
+// (or expert) l % 16 and reduction index 4*(l / 16) + s within a piece of 16.
+// Both operands come through LDS: wide coalesced loads one chunk ahead, double
+// buffered, one barrier per chunk.  Wavefronts of different groups own
+// different experts; the PARTS wavefronts of a group add their partial sums
+// into LDS one after the other (fixed order: deterministic).
+template <typename ET, int NBW, int PARTS>
+__device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem) {
     typedef RouteLoad<ET> L;
     typedef typename L::x4_t x4_t;
-    typedef typename L::raw_t raw_t;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int ES = (int)sizeof(ET);
+    constexpr int GROUPS = 4 / PARTS;
+    constexpr int MAXPW = 5, MAXPX = 2;  // 16-byte pieces of a chunk per thread: 20 KB, 8 KB
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int E = a.E, d = a.d;
+    const RouteShape rs = route_shape(E, ES);
     const int li = lane & 15, kq = lane >> 4;
+    const int g = wave % GROUPS, part = wave / GROUPS;
     double *lg = (double *)smem;  // [16][E]
-    const ET *x = (const ET *)a.x;
-    const ET *Wg = (const ET *)a.Wg;
-    const int nchunk = d / 16;
-    const int c_begin = (nchunk * wave) / 4, c_end = (nchunk * (wave + 1)) / 4;
-    const int tok = min(t0 + li, a.T - 1);
-    const ET *xrow = x + (size_t)tok * d + 4 * kq;
-    // expert column of this lane in block eb0 + eb; lanes past E re-read a valid column and are masked
-    bool live[NB];
-    const ET *wcol[NB];
+    char *stage = smem + (size_t)kRouteTokens * E * 8;
+    const int stage_bytes = (int)route_stage_bytes(rs);
+    const int x_off = rs.KC * rs.RS;  // x rows follow the weight rows of a buffer
+    const char *x = (const char *)a.x;
+    const char *Wg = (const char *)a.Wg;
+    const int row_bytes = E * ES;
+    const bool wide = (row_bytes % 16) == 0;
+    const int ppr = row_bytes / 16;
+    const int nchunk = (d + rs.KC - 1) / rs.KC;
+
+    // this wavefront's expert columns; lanes past E read a valid column and are masked
+    u32 keep[NBW];
+    int col_off[NBW];
 #pragma unroll
-    for (int eb = 0; eb < NB; ++eb) {
-        const int e = (eb0 + eb) * 16 + li;
-        live[eb] = e < E;
-        wcol[eb] = Wg + (size_t)(4 * kq) * E + (live[eb] ? e : 0);
+    for (int b = 0; b < NBW; ++b) {
+        const int e = (g + b * GROUPS) * 16 + li;
+        keep[b] = e < E ? ~0u : 0u;
+        col_off[b] = (e < E ? e : 0) * ES;
     }
+    f64x4_t acc[NBW];
+#pragma unroll
+    for (int b = 0; b < NBW; ++b) acc[b] = f64x4_t{0.0, 0.0, 0.0, 0.0};
 
-    f64x4_t acc[NB];
+    u32x4_t prew[MAXPW], prex[MAXPX];
+    auto fetch = [&](int c) __attribute__((always_inline)) {  // chunk c -> registers
+        const int k0 = c * rs.KC, rows = min(rs.KC, d - k0);
+        if (wide) {
 #pragma unroll
-    for (int eb = 0; eb < NB; ++eb) acc[eb] = f64x4_t{0.0, 0.0, 0.0, 0.0};
-
-    struct Raw {
-        x4_t xv[U];
-        raw_t w[U][4][NB];
-    };
-    auto load = [&](int c0, Raw &r) {
+            for (int i = 0; i < MAXPW; ++i) {
+                const int q = tid + i * kThreads;
+                if (q < rows * ppr) prew[i] = *(const u32x4_t *)(Wg + (size_t)(k0 + q / ppr) * row_bytes + (q % ppr) * 16);
+            }
+        }
+        const int ppx = rows * ES / 16;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int c = min(c0 + u, c_end - 1);  // past the end: re-read the last chunk, masked in mul()
-            r.xv[u] = *(const x4_t *)(xrow + c * 16);
-#pragma unroll
-            for (int s = 0; s < 4; ++s)
-#pragma unroll
-                for (int eb = 0; eb < NB; ++eb) r.w[u][s][eb] = L::load_raw(wcol[eb] + (size_t)(c * 16 + s) * E);
+        for (int i = 0; i < MAXPX; ++i) {
+            const int q = tid + i * kThreads;
+            if (q < kRouteTokens * ppx) {
+                const int tok = min(t0 + q / ppx, a.T - 1);
+                prex[i] = *(const u32x4_t *)(x + ((size_t)tok * d + k0) * ES + (q % ppx) * 16);
+            }
         }
     };
-    auto mul = [&](int c0, const Raw &r) {
+    auto store = [&](int c, int buf) __attribute__((always_inline)) {  // registers -> LDS buffer
+        const int k0 = c * rs.KC, rows = min(rs.KC, d - k0);
+        char *dst = stage + buf * stage_bytes;
+        if (wide) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const bool in = c0 + u < c_end;
+            for (int i = 0; i < MAXPW; ++i) {
+                const int q = tid + i * kThreads;
+                if (q < rows * ppr) *(u32x4_t *)(dst + (q / ppr) * rs.RS + (q % ppr) * 16) = prew[i];
+            }
+        } else {  // odd row sizes (tiny expert counts): element by element, straight from global memory
+            for (int q = tid; q < rows * E; q += kThreads)
+                *(ET *)(dst + (q / E) * rs.RS + (q % E) * ES) = *(const ET *)(Wg + ((size_t)(k0 + q / E) * E + q % E) * ES);
+        }
+        const int ppx = rows * ES / 16;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const double av = in ? L::get(r.xv[u], s) : 0.0;
+        for (int i = 0; i < MAXPX; ++i) {
+            const int q = tid + i * kThreads;
+            if (q < kRouteTokens * ppx) *(u32x4_t *)(dst + x_off + (q / ppx) * rs.XRS + (q % ppx) * 16) = prex[i];
+        }
+    };
+    auto mul = [&](int c, int buf) __attribute__((always_inline)) {
+        const int pieces = min(rs.KC, d - c * rs.KC) / 16;
+        const char *src = stage + buf * stage_bytes;
+        const char *xs = src + x_off + li * rs.XRS + 4 * kq * ES;
+        for (int u = part; u < pieces; u += PARTS) {
+            const x4_t xv = *(const x4_t *)(xs + 16 * u * ES);
 #pragma unroll
-                for (int eb = 0; eb < NB; ++eb) {
-                    const double bv = live[eb] ? L::to_double(r.w[u][s][eb]) : 0.0;
-                    acc[eb] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[eb], 0, 0, 0);
+            for (int s2 = 0; s2 < 4; ++s2) {
+                const double av = L::get(xv, s2);
+                const char *wrow = src + (16 * u + 4 * kq + s2) * rs.RS;
+#pragma unroll
+                for (int b = 0; b < NBW; ++b) {
+                    const double bv = L::to_double(*(const ET *)(wrow + col_off[b]), keep[b]);
+                    acc[b] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[b], 0, 0, 0);
                 }
             }
         }
     };
-    Raw r0, r1;
-    if (c_begin < c_end) {
-        load(c_begin, r0);
-        for (int c = c_begin; c < c_end; c += 2 * U) {
-            load(c + U, r1);
-            mul(c, r0);
-            load(c + 2 * U, r0);
-            mul(c + U, r1);
-        }
+
+    fetch(0);
+    store(0, 0);
+    __syncthreads();
+    for (int c = 0; c < nchunk; ++c) {
+        const int buf = c & 1;
+        if (c + 1 < nchunk) fetch(c + 1);
+        mul(c, buf);
+        if (c + 1 < nchunk) store(c + 1, buf ^ 1);
+        __syncthreads();
     }
     // D layout: lane l, register v -> token 4*v + l/16, expert (block) l % 16
-    for (int w = 0; w < 4; ++w) {
-        if (wave == w) {
+    for (int p2 = 0; p2 < PARTS; ++p2) {
+        if (part == p2) {
 #pragma unroll
-            for (int eb = 0; eb < NB; ++eb) {
-                const int e = (eb0 + eb) * 16 + li;
+            for (int b = 0; b < NBW; ++b) {
+                const int e = (g + b * GROUPS) * 16 + li;
                 if (e < E) {
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int t = 4 * v + kq;
-                        const double prev = (w == 0) ? (a.bias ? (double)a.bias[e] : 0.0) : lg[t * E + e];
-                        lg[t * E + e] = prev + acc[eb][v];
+                        const double prev = (p2 == 0) ? (a.bias ? (double)a.bias[e] : 0.0) : lg[t * E + e];
+                        lg[t * E + e] = prev + acc[b][v];
                     }
                 }
             }
@@ -144,27 +213,36 @@ __device__ void route_logits(const KArgs &a, int t0, int eb0, char *smem) {
 }
 
 template <typename ET>
-__device__ void route_logits_dispatch(const KArgs &a, int t0, char *smem) {
-    const int nb = (a.E + 15) / 16;
-    if (nb <= 1)
-        route_logits<ET, 1, 8>(a, t0, 0, smem);
-    else if (nb <= 2)
-        route_logits<ET, 2, 4>(a, t0, 0, smem);
-    else if (nb <= 4)
-        route_logits<ET, 4, 2>(a, t0, 0, smem);
+__device__ __forceinline__ void route_logits_dispatch(const KArgs &a, int t0, char *smem) {
+    const RouteShape rs = route_shape(a.E, (int)sizeof(ET));
+    if (rs.parts == 4)
+        route_logits<ET, 1, 4>(a, t0, smem);
+    else if (rs.parts == 2) {
+        if (rs.nbw == 1)
+            route_logits<ET, 1, 2>(a, t0, smem);
+        else
+            route_logits<ET, 2, 2>(a, t0, smem);
+    } else if (rs.nbw == 1)
+        route_logits<ET, 1, 1>(a, t0, smem);
+    else if (rs.nbw == 2)
+        route_logits<ET, 2, 1>(a, t0, smem);
+    else if (rs.nbw == 3)
+        route_logits<ET, 3, 1>(a, t0, smem);
     else
-        for (int eb0 = 0; eb0 < nb; eb0 += 8) route_logits<ET, 8, 1>(a, t0, eb0, smem);  // 128 experts per pass
+        route_logits<ET, 4, 1>(a, t0, smem);
 }
 
 // One gate task: tokens [task*16, task*16+16).  With a.Wg == NULL the routing
 // is an input and only the histograms are produced.
 template <typename ET>
-__device__ void route_task(const KArgs &a, int task, char *smem, bool do_hist) {
+__device__ __forceinline__ void route_task(const KArgs &a, int task, char *smem, bool do_hist) {
     const int t0 = task * kRouteTokens;
     const int E = a.E, k = a.k;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool compute = (a.Wg != nullptr);
+    MOE_TT_BEGIN();
     if (compute) route_logits_dispatch<ET>(a, t0, smem);
+    MOE_TT(a.ctrl, 32);
     const double *lg = (const double *)smem;
     const double NEG = -__builtin_huge_val();
 
@@ -221,6 +299,7 @@ __device__ void route_task(const KArgs &a, int task, char *smem, bool do_hist) {
             }
         }
     }
+    MOE_TT(a.ctrl, 33);
 }
 
 }  // namespace moe
