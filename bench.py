@@ -65,6 +65,43 @@ def cpu_baseline(inp, budget_tokens: int):
             "sample": f"first {n} of {cfg['T']} tokens of the same workload, whole path, {dt:.1f} s"}
 
 
+def standalone_ops(B, torch, p, buf, dev, cfg, steps):
+    """Average duration of each standalone entry point (HIP events on the launch stream) and the
+    rate at which it moves its algorithmic bytes.  buf holds the routing of the last full pass."""
+    T, d, E, k = cfg["T"], cfg["d"], cfg["E"], cfg["k"]
+    sz = 4 if cfg["dtype"] == "f32" else 2
+    N = T * k
+    x_perm = torch.empty((N, d), dtype=dev["x"].dtype, device="cuda")
+    idx2, w2 = torch.empty_like(buf.topk_idx), torch.empty_like(buf.topk_w)
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for e0, e1 in evs:
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        return sum(e0.elapsed_time(e1) for e0, e1 in evs) / steps
+
+    out = {}
+    if dev["Wg"] is not None:
+        ms = timed(lambda: B.moe_route(p, dev["x"], dev["Wg"], dev["gate_bias"], idx2, w2))
+        out["moe_route"] = {"ms": ms, "fp64_tflops": 2.0 * T * d * E / (ms * 1e-3) / 1e12}
+    ms = timed(lambda: B.moe_dispatch(p, dev["x"], buf.topk_idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm,
+                                      x_perm, buf.workspace))
+    nbytes = 2 * N * d * sz + 12 * N  # rows read and written once, indices read, perm and inv_perm written
+    out["moe_dispatch"] = {"ms": ms, "algorithmic_bytes": nbytes, "GB/s": nbytes / (ms * 1e-3) / 1e9,
+                           "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    ms = timed(lambda: B.moe_combine(p, buf.staging, None, None, buf.topk_w, buf.out, None))
+    nbytes = N * d * sz + T * d * sz + 4 * N  # staging rows read, out written, weights read
+    out["moe_combine"] = {"ms": ms, "algorithmic_bytes": nbytes, "GB/s": nbytes / (ms * 1e-3) / 1e9,
+                          "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -78,6 +115,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic) so that hardware byte "
                          "counters collected around this command can be scaled")
+    ap.add_argument("--ops", action="store_true",
+                    help="also time the standalone entry points (moe_route, moe_dispatch, moe_combine) on the same "
+                         "workload and add them to the JSON line as 'standalone_ops'")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -153,6 +193,8 @@ def main():
                         "gemm1_end": stats[11] / 1e3, "gemm2_end": stats[12] / 1e3, "combine_end": stats[13] / 1e3,
                         "wait_sum": stats[14] / 1e3, "workgroups": stats[15]},
     }
+    if args.ops:
+        res["standalone_ops"] = standalone_ops(B, torch, p, buf, dev, cfg, args.steps)
     if not args.no_cpu:
         n_cpu = args.cpu_tokens or max(16, min(cfg["T"], int(4e11 / (cfg["k"] * 3 * cfg["d"] * cfg["f"]))))
         res["cpu_baseline"] = cpu_baseline(inp, n_cpu)

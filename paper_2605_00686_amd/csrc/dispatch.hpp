@@ -19,19 +19,41 @@ __host__ __device__ inline size_t plan_smem_bytes(int E, int R, int nPB) {
     return n;
 }
 
+// Exclusive prefix sum by ONE wavefront over n values src[0], src[stride], ... (LDS or global),
+// written to dst at the same positions; returns the total.  src == dst is allowed.
+__device__ __forceinline__ int wave_exclusive_scan(const int32_t *src, int32_t *dst, int n, int stride, int start) {
+    const int lane = threadIdx.x & 63;
+    int carry = start;
+    for (int base = 0; base < n; base += 64) {
+        const int i = base + lane;
+        const int x = i < n ? src[(size_t)i * stride] : 0;
+        int inc = x;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(inc, off, 64);
+            if (lane >= off) inc += o;
+        }
+        if (i < n) dst[(size_t)i * stride] = carry + inc - x;
+        carry += __shfl(inc, 63, 64);
+    }
+    return carry;
+}
+
 // Single-workgroup task.  Reads blk_hist[nPB][E] and seg_cnt[E][R] (complete),
 // writes counts, offsets, blk_base, seg_begin, flag_base, dest_flag_begin,
 // rb_base, rb_expert, ctrl->n_rb, ctrl->n_flags.  The inputs are first copied
-// to LDS with coalesced loads so that the serial scans below never wait on a
-// global load.
+// to LDS with coalesced loads; every scan then runs either one thread per
+// sequence (many short sequences) or one wavefront per sequence with a shuffle
+// scan (few long ones), so that nothing walks a long sequence serially.
 __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int E = a.E, R = a.R, nPB = a.nPB;
     int32_t *s_cnt = (int32_t *)smem;  // [E]
     int32_t *s_off = s_cnt + E;        // [E+1]
     int32_t *s_dest = s_off + E + 1;   // [R+1] flags per destination, then their scan
-    int32_t *s_rb = s_dest + R + 1;    // [E+1]
+    int32_t *s_rb = s_dest + R + 1;    // [E+1] row blocks per expert, then their scan
     int32_t *s_free = s_rb + E + 2;
+    MOE_TT_BEGIN();
     const bool seg_lds = plan_seg_in_lds(E, R), hist_lds = plan_hist_in_lds(nPB, E);
     int32_t *segc = a.seg_cnt, *segb = a.seg_begin, *hist = a.blk_base, *nfl = a.flag_base;
     // tile_m and the row-block height are powers of two
@@ -43,35 +65,39 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
         s_free = nfl + E * R;
         for (int q = tid; q < E * R; q += kThreads) segc[q] = a.seg_cnt[q];
     }
-    if (hist_lds) {
-        hist = s_free;
-        for (int q = tid; q < nPB * E; q += kThreads) hist[q] = a.blk_hist[q];
-    } else {
-        for (int q = tid; q < nPB * E; q += kThreads) hist[q] = a.blk_hist[q];  // blk_base <- blk_hist
-    }
+    if (hist_lds) hist = s_free;
+    for (int q = tid; q < nPB * E; q += kThreads) hist[q] = a.blk_hist[q];  // (blk_base <- blk_hist if not in LDS)
     __syncthreads();
+    MOE_TT(a.ctrl, 34);
     // per expert: rows per destination -> first row of each (e, r) segment and the total
-    for (int e = tid; e < E; e += kThreads) {
-        int sb = 0;
-        for (int r = 0; r < R; ++r) {
-            const int c = segc[e * R + r];
-            segb[e * R + r] = sb;
-            sb += c;
+    if (R <= 16) {
+        for (int e = tid; e < E; e += kThreads) {
+            int sb = 0;
+            for (int r = 0; r < R; ++r) {
+                const int c = segc[e * R + r];
+                segb[e * R + r] = sb;
+                sb += c;
+            }
+            s_cnt[e] = sb;
         }
-        s_cnt[e] = sb;
+    } else {
+        for (int e = wave; e < E; e += 4) {
+            const int total = wave_exclusive_scan(segc + (size_t)e * R, segb + (size_t)e * R, R, 1, 0);
+            if (lane == 0) s_cnt[e] = total;
+        }
     }
     __syncthreads();
-    if (tid == 0) {
-        int run = 0, rb = 0;
-        for (int e = 0; e < E; ++e) {
-            s_off[e] = run;
-            s_rb[e] = rb;
-            run += s_cnt[e];
-            rb += (s_cnt[e] + a.tl.BM - 1) >> lbm;
+    // rows and row blocks: exclusive scans over the experts
+    for (int e = tid; e < E; e += kThreads) s_rb[e] = (s_cnt[e] + a.tl.BM - 1) >> lbm;
+    __syncthreads();
+    if (wave == 0) {
+        const int rows = wave_exclusive_scan(s_cnt, s_off, E, 1, 0);
+        const int rb = wave_exclusive_scan(s_rb, s_rb, E, 1, 0);
+        if (lane == 0) {
+            s_off[E] = rows;
+            s_rb[E] = rb;
+            a.ctrl->n_rb = (u32)rb;
         }
-        s_off[E] = run;
-        s_rb[E] = rb;
-        a.ctrl->n_rb = (u32)rb;
     }
     __syncthreads();
     for (int e = tid; e <= E; e += kThreads) {
@@ -82,18 +108,24 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
             for (int i = s_rb[e]; i < s_rb[e + 1]; ++i) a.rb_expert[i] = e;
         }
     }
+    MOE_TT(a.ctrl, 35);
     // sorted position of each block's first slot of e: exclusive scan over blocks
-    for (int e = tid; e < E; e += kThreads) {
-        int run = s_off[e];
-        for (int b = 0; b < nPB; ++b) {
-            const int c = hist[b * E + e];
-            hist[b * E + e] = run;
-            run += c;
+    if (E >= 64) {
+        for (int e = tid; e < E; e += kThreads) {
+            int run = s_off[e];
+            for (int b = 0; b < nPB; ++b) {
+                const int c = hist[b * E + e];
+                hist[b * E + e] = run;
+                run += c;
+            }
         }
+    } else {
+        for (int e = wave; e < E; e += 4) wave_exclusive_scan(hist + e, hist + e, nPB, E, s_off[e]);
     }
+    MOE_TT(a.ctrl, 36);
     // flags: destination-major, then expert; a segment with expert-local rows
     // [b0, b0+c) touches row blocks b0/tile_m .. (b0+c-1)/tile_m.  All (r, e)
-    // pairs in parallel, then one short scan per destination.
+    // pairs in parallel, then one scan per destination.
     for (int q = tid; q < E * R; q += kThreads) {
         const int r = q / E, e = q - r * E;
         const int c = segc[e * R + r];
@@ -105,27 +137,32 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
         nfl[q] = n;
     }
     __syncthreads();
-    for (int r = tid; r < R; r += kThreads) {
-        int run = 0;
-        for (int e = 0; e < E; ++e) {
-            const int n = nfl[r * E + e];
-            nfl[r * E + e] = run;  // exclusive within the destination
-            run += n;
+    if (R <= 16) {
+        for (int r = wave; r < R; r += 4) {
+            const int total = wave_exclusive_scan(nfl + (size_t)r * E, nfl + (size_t)r * E, E, 1, 0);
+            if (lane == 0) s_dest[r] = total;
         }
-        s_dest[r] = run;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        int run = 0;
-        for (int r = 0; r < R; ++r) {
-            const int n = s_dest[r];
+    } else {
+        for (int r = tid; r < R; r += kThreads) {
+            int run = 0;
+            for (int e = 0; e < E; ++e) {
+                const int n = nfl[r * E + e];
+                nfl[r * E + e] = run;  // exclusive within the destination
+                run += n;
+            }
             s_dest[r] = run;
-            run += n;
         }
-        s_dest[R] = run;
-        a.ctrl->n_flags = (u32)run;
     }
     __syncthreads();
+    if (wave == 0) {
+        const int total = wave_exclusive_scan(s_dest, s_dest, R, 1, 0);
+        if (lane == 0) {
+            s_dest[R] = total;
+            a.ctrl->n_flags = (u32)total;
+        }
+    }
+    __syncthreads();
+    MOE_TT(a.ctrl, 37);
     if (hist_lds)
         for (int q = tid; q < nPB * E; q += kThreads) a.blk_base[q] = hist[q];
     if (seg_lds)
@@ -133,6 +170,7 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
     for (int q = tid; q < E * R; q += kThreads) a.flag_base[q] = nfl[q] + s_dest[q / E];
     for (int r = tid; r <= R; r += kThreads) a.dest_flag_begin[r] = s_dest[r];
     __syncthreads();
+    MOE_TT(a.ctrl, 38);
 }
 
 // One permutation block: tokens [b*64, b*64+64).  The k experts of a token are

@@ -44,7 +44,7 @@ constexpr int tile_smem_bytes() {
 // stage depth / count per shape: the best of the variants measured on MI355X
 using CfgL = TileCfg<4, 4, 2, 2, 32, 4>;  // 256 x 256, wavefront 128 x 128
 using CfgM = TileCfg<2, 4, 2, 2, 64, 3>;  // 128 x 256, wavefront  64 x 128
-using CfgS = TileCfg<1, 2, 1, 4, 64, 2>;  //  32 x 256, wavefront  32 x  64, two workgroups per CU
+using CfgS = TileCfg<1, 2, 1, 4, 64, 4>;  //  32 x 256, wavefront  32 x  64, deep pipeline: weight streaming
 
 struct TileInfo {
     int e, rb, row0, nrows, lrow0, n0, ncols;

@@ -83,6 +83,9 @@ __device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
             phase = 1;
             if (tid == 0) sl->ok = wait_ge(c, &c->route_done, (u32)a.nRT) ? 1 : 0;
             __syncthreads();
+#ifdef MOE_TILE_TIMING
+            if (tid == 0) c->dbg[39] = now_ticks() - c->t0;
+#endif
             if (sl->ok) plan_task(a, smem);
             sync_stores();
             if (tid == 0) {
@@ -225,6 +228,9 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
                    c->dbg[12] / n2 / 100., c->dbg[13] / n2 / 100., c->dbg[10] / (n1 + n2) / 100.);
             printf("gate (us/task, thread 0): logits %.2f, top-k and histograms %.2f\n", c->dbg[32] / (double)a.nRT / 100.,
                    c->dbg[33] / (double)a.nRT / 100.);
+            printf("plan starts at %.2f us; ", c->dbg[39] / 100.);
+            printf("plan (us): stage %.2f, expert scans %.2f, block scan %.2f, flags %.2f, write-back %.2f\n", c->dbg[34] / 100.,
+                   c->dbg[35] / 100., c->dbg[36] / 100., c->dbg[37] / 100., c->dbg[38] / 100.);
             printf("tiles done (us): avg over workgroups %.1f, last %.1f; per queue g1 end", c->dbg[14] / (double)gridDim.x / 100., c->dbg[15] / 100.);
             for (int q = 0; q < 8; ++q) printf(" %.0f", c->dbg[16 + q] / 100.);
             printf("; g2 end");

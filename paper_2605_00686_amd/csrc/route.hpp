@@ -11,26 +11,25 @@ typedef __attribute__((ext_vector_type(4))) u32 u32x4_t;  // 16 bytes in registe
 
 // How a gate task lays out its work.  The gate weights and the task's 16 rows
 // of x pass through LDS in chunks of KC reduction indices (weights: row stride
-// RS bytes, x: row stride XRS bytes, both padded so that the rows a wavefront
-// reads at once fall into different banks); the E/16 expert blocks are dealt to
-// `groups` groups of wavefronts, and the `parts` wavefronts of a group take
+// RS bytes, x: row stride XRS bytes), two buffers, the next chunk in flight
+// while this one multiplies.  A chunk is made as large as LDS allows (72 KB in
+// all, so that two workgroups still share a CU): its multiplications then
+// outlast the trip to memory of the next one.  The E/16 expert blocks are dealt
+// to `groups` groups of wavefronts, and the `parts` wavefronts of a group take
 // alternate 16-index pieces of every chunk.
+constexpr int kRouteLds = 72 * 1024;
+constexpr int kRouteMaxKC = 512;
 struct RouteShape {
     int RS, XRS, KC, nb, groups, parts, nbw;
 };
-__host__ __device__ inline int route_pad_row(int bytes, int target_dw) {
-    const int dw = (bytes + 3) / 4;
-    return 4 * (dw + (((target_dw - dw) % 64) + 64) % 64);
-}
 __host__ __device__ inline RouteShape route_shape(int E, int elem_size) {
     RouteShape r;
-    const int target = (elem_size == 2) ? 8 : 16;  // dwords one 16-lane read covers
-    r.RS = route_pad_row(E * elem_size, target);
-    const int xlim = 8 * 1024 / (kRouteTokens * elem_size);  // x chunk of at most 8 KB
-    r.KC = (16 * 1024 / r.RS) / 16 * 16;                     // weight chunk of about 16 KB
-    if (r.KC > xlim) r.KC = xlim;
+    r.RS = (E * elem_size + 15) / 16 * 16;
+    const int budget = (kRouteLds - kRouteTokens * E * 8) / 2;  // bytes per buffer
+    r.KC = budget / (r.RS + kRouteTokens * elem_size) / 16 * 16;
+    if (r.KC > kRouteMaxKC) r.KC = kRouteMaxKC;
     if (r.KC < 16) r.KC = 16;
-    r.XRS = route_pad_row(r.KC * elem_size, target);
+    r.XRS = r.KC * elem_size;
     r.nb = (E + 15) / 16;
     r.groups = r.nb >= 4 ? 4 : r.nb >= 2 ? 2 : 1;
     r.parts = 4 / r.groups;
@@ -93,7 +92,7 @@ __device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem)
     typedef typename L::x4_t x4_t;
     constexpr int ES = (int)sizeof(ET);
     constexpr int GROUPS = 4 / PARTS;
-    constexpr int MAXPW = 5, MAXPX = 2;  // 16-byte pieces of a chunk per thread: 20 KB, 8 KB
+    constexpr int MAXPW = 7, MAXPX = 8;  // 16-byte pieces of a chunk per thread (the most route_shape() can ask for)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int E = a.E, d = a.d;
     const RouteShape rs = route_shape(E, ES);

@@ -5,7 +5,8 @@ method's arithmetic (no routing, no sorting, no expert math), so both the HIP
 path and the CPU oracle may be fed from it without sharing code.
 
 Shapes follow Table 1 of the paper (H, I, E, k): Qwen3-30B-A3B
-(2048, 768, 128, 8) and DeepSeek-V3 (7168, 2048, 256, 8), plus a compute-bound
+(2048, 768, 128, 8), DeepSeek-V3 (7168, 2048, 256, 8) and GPT-OSS-120B
+(2880, 2880, 128, 4), plus a compute-bound
 few-large-experts layer in the role the paper gives Llama4 (section 3.1) and a
 decode-sized batch (section 8, 'small S resembles decode').  Skewed routing
 follows section 6.4 (Zipf popularity, no token drops).
@@ -29,6 +30,8 @@ CONFIGS = {
     "cfg4": dict(T=16384, d=4096, E=8, k=2, f=14336, R=8, dtype="bf16", seed=4),
     # decode-sized batch, many tiny signaled tiles
     "cfg5": dict(T=128, d=7168, E=32, k=8, f=2048, R=64, dtype="bf16", seed=5, tile_m=32),
+    # third shape of Table 1 (2880, 2880, 128, 4): dimensions that are not powers of two, ragged column tiles
+    "cfg6": dict(T=4096, d=2880, E=128, k=4, f=2880, R=8, dtype="bf16", seed=6),
     # --- reduced shapes for parity tests: several tiles plus ragged tails ---
     "mini_f32": dict(T=96, d=192, E=6, k=2, f=320, R=4, dtype="f32", seed=11),
     "mini_bf16": dict(T=384, d=512, E=8, k=2, f=640, R=4, dtype="bf16", seed=12, bias_std=0.5),
@@ -37,6 +40,7 @@ CONFIGS = {
                      prerouted=dict(global_experts=256, zipf=1.1, topk=8)),
     "mini_large": dict(T=2048, d=512, E=4, k=2, f=384, R=8, dtype="bf16", seed=16),
     "mini_decode": dict(T=64, d=1024, E=16, k=4, f=512, R=32, dtype="bf16", seed=15, tile_m=32),
+    "mini_odd": dict(T=320, d=320, E=8, k=4, f=448, R=4, dtype="bf16", seed=17),
 }
 
 W_STD = 0.02  # N(0, 0.02): 0.02 is the standard deviation

@@ -13,7 +13,7 @@ from tests import parity
 
 pytestmark = pytest.mark.gpu
 
-SAMPLES = {"cfg1": 256, "cfg2": 48, "cfg3": 48, "cfg4": 12, "cfg5": 24}
+SAMPLES = {"cfg1": 256, "cfg2": 48, "cfg3": 48, "cfg4": 12, "cfg5": 24, "cfg6": 24}
 
 
 def _run(name, signal_mode, fence_scope, inp=None, buf=None, epoch=1):
@@ -79,7 +79,7 @@ def _check(B, inp, p, buf, signal_mode, name, cache):
     print(f"{name} mode {signal_mode}: min margin {mm} staging {m1} out {m2} stats {stats.tolist()}", flush=True)
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg5", "cfg4"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg5", "cfg6", "cfg4"])
 def test_fullsize_parity(name):
     print(f"case full-size {name}", flush=True)
     cache = {}

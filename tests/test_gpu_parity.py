@@ -79,7 +79,7 @@ def check_against_oracle(B, inp, p, buf, signal_mode, ref=None):
     return ref
 
 
-@pytest.mark.parametrize("name", ["mini_f32", "mini_bf16", "mini_skew", "mini_pre", "mini_decode", "mini_large"])
+@pytest.mark.parametrize("name", ["mini_f32", "mini_bf16", "mini_skew", "mini_pre", "mini_decode", "mini_large", "mini_odd"])
 @pytest.mark.parametrize("signal_mode", [0, 1])
 def test_megakernel_parity(name, signal_mode):
     B = _binding()
