@@ -6,7 +6,7 @@ publish with flags, combine) in one persistent-kernel launch over one batch of
 seeded synthetic input already resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
-                  [--signal-mode per_dest|per_tile] [--scope agent|system] [--no-cpu]
+                  [--signal-mode per_dest|per_tile] [--scope agent|system] [--group-size G] [--ops] [--no-cpu]
 """
 from __future__ import annotations
 
@@ -110,6 +110,8 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--signal-mode", default="per_dest", choices=["per_dest", "per_tile"])
     ap.add_argument("--scope", default="agent", choices=["agent", "system"])
+    ap.add_argument("--group-size", type=int, default=0,
+                    help="per_dest only: flags per fence group (0 = all flags of a destination)")
     ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens for the CPU baseline (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -133,7 +135,7 @@ def main():
     mode = B.MOE_SIGNAL_PER_DEST if args.signal_mode == "per_dest" else B.MOE_SIGNAL_PER_TILE
     scope = B.MOE_SCOPE_AGENT if args.scope == "agent" else B.MOE_SCOPE_SYSTEM
     p = B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
-                  tile_n=cfg["tile_n"], signal_mode=mode, fence_scope=scope, epoch=1)
+                  tile_n=cfg["tile_n"], signal_mode=mode, fence_scope=scope, epoch=1, group_size=args.group_size)
     buf = B.Buffers(p)
     dev = {n: (inp[n].cuda() if inp[n] is not None else None) for n in ("x", "Wg", "gate_bias", "W1", "W3", "W2")}
     if cfg["prerouted"] is not None:
@@ -180,7 +182,8 @@ def main():
         "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: T={cfg['T']} d={cfg['d']} E={cfg['E']} k={cfg['k']} f={cfg['f']} "
                                f"R={cfg['R']} tile={cfg['tile_m']}x{cfg['tile_n']}",
-                   "signal_mode": args.signal_mode, "fence_scope": args.scope, "launches_per_step": 1},
+                   "signal_mode": args.signal_mode, "fence_scope": args.scope, "group_size": args.group_size,
+                   "launches_per_step": 1},
         "roofline": {"bound": "hbm", "kernel": "k_megakernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                      "algorithmic_bytes": abytes, "kernel_ms_avg": avg_ms, "kernel_ms_median": kern_ms[len(kern_ms) // 2],

@@ -72,6 +72,13 @@ typedef struct {
     int32_t fence_scope;      /* moe_fence_scope_t                                  */
     uint32_t epoch;           /* value a flag takes when its tile is ready; nonzero */
                               /* and different from the previous call's             */
+    int32_t group_size;       /* MOE_SIGNAL_PER_DEST only: flags per fence group    */
+                              /* (section 4.1, granularity of Algorithm 1).  0 = all */
+                              /* flags of a destination form one group (the paper's */
+                              /* per-destination default); g >= 1 = groups of g     */
+                              /* consecutive flags of a destination, one fence per  */
+                              /* group: fences = sum over r of ceil(n_r / g).  Must */
+                              /* be 0 for MOE_SIGNAL_PER_TILE                       */
 } moe_problem_t;
 
 /* number of 64-bit counters moe_megakernel_forward writes to `stats` */

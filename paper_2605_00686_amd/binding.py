@@ -26,7 +26,8 @@ EXPORTS = ("moe_workspace_bytes", "moe_num_flags", "moe_status_string", "moe_wor
 
 class MoeProblem(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("T", "d", "E", "k", "f", "R", "dtype", "tile_m", "tile_n",
-                                              "signal_mode", "fence_scope")] + [("epoch", ctypes.c_uint32)]
+                                              "signal_mode", "fence_scope")] + [("epoch", ctypes.c_uint32),
+                                                                                 ("group_size", ctypes.c_int32)]
 
 
 class MoeError(RuntimeError):
@@ -55,12 +56,12 @@ for _n in ("moe_workspace_init", "moe_route", "moe_dispatch", "moe_megakernel_fo
 
 
 def problem(T, d, E, k, f, R, dtype, tile_m=0, tile_n=0, signal_mode=MOE_SIGNAL_PER_DEST,
-            fence_scope=MOE_SCOPE_AGENT, epoch=1) -> MoeProblem:
+            fence_scope=MOE_SCOPE_AGENT, epoch=1, group_size=0) -> MoeProblem:
     if isinstance(dtype, torch.dtype):
         dtype = MOE_DT_F32 if dtype == torch.float32 else MOE_DT_BF16
     elif isinstance(dtype, str):
         dtype = MOE_DT_F32 if dtype == "f32" else MOE_DT_BF16
-    return MoeProblem(T, d, E, k, f, R, dtype, tile_m, tile_n, signal_mode, fence_scope, epoch)
+    return MoeProblem(T, d, E, k, f, R, dtype, tile_m, tile_n, signal_mode, fence_scope, epoch, group_size)
 
 
 def _ptr(t):

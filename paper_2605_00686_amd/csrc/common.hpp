@@ -54,6 +54,7 @@ struct Tiling {
 struct KArgs {
     int T, d, E, k, f, R;
     int dtype, tile_m, tile_n, signal_mode, fence_scope;
+    int group_size;  // flags per fence group of the per-destination mode, 0 = all flags of a destination
     u32 epoch;
     int N, per_dest, ncb;  // slots, tokens per destination, column blocks per row
     int nPB, nRT, nCT;     // permutation blocks, gate tasks, combine tasks
@@ -83,7 +84,8 @@ struct KArgs {
     int32_t *seg_begin;        // [E][R] expert-local first row of (e, r)
     int32_t *flag_base;        // [R][E]
     int32_t *dest_flag_begin;  // [R+1]
-    u32 *dest_counter;         // [R] publish tiles written so far (PER_DEST)
+    int32_t *dest_group_begin; // [R+1] first fence group of destination r
+    u32 *group_counter;        // [fence groups] publish tiles written so far (PER_DEST)
     int32_t *rb_base;          // [E+1] first row block of expert e
     int32_t *rb_expert;        // [maxRB]
     u32 *h_ready;              // [maxRB] GEMM1 tiles finished per row block

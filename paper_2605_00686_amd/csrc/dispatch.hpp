@@ -13,7 +13,7 @@ constexpr size_t kPlanSegLds = 48 * 1024, kPlanHistLds = 32 * 1024;
 __host__ __device__ inline bool plan_seg_in_lds(int E, int R) { return (size_t)3 * E * R * 4 <= kPlanSegLds; }
 __host__ __device__ inline bool plan_hist_in_lds(int nPB, int E) { return (size_t)nPB * E * 4 <= kPlanHistLds; }
 __host__ __device__ inline size_t plan_smem_bytes(int E, int R, int nPB) {
-    size_t n = (size_t)(3 * E + R + 8) * 4;
+    size_t n = (size_t)(3 * E + 2 * R + 10) * 4;
     if (plan_seg_in_lds(E, R)) n += (size_t)3 * E * R * 4;
     if (plan_hist_in_lds(nPB, E)) n += (size_t)nPB * E * 4;
     return n;
@@ -40,7 +40,7 @@ __device__ __forceinline__ int wave_exclusive_scan(const int32_t *src, int32_t *
 }
 
 // Single-workgroup task.  Reads blk_hist[nPB][E] and seg_cnt[E][R] (complete),
-// writes counts, offsets, blk_base, seg_begin, flag_base, dest_flag_begin,
+// writes counts, offsets, blk_base, seg_begin, flag_base, dest_flag_begin, dest_group_begin,
 // rb_base, rb_expert, ctrl->n_rb, ctrl->n_flags.  The inputs are first copied
 // to LDS with coalesced loads; every scan then runs either one thread per
 // sequence (many short sequences) or one wavefront per sequence with a shuffle
@@ -52,7 +52,8 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
     int32_t *s_off = s_cnt + E;        // [E+1]
     int32_t *s_dest = s_off + E + 1;   // [R+1] flags per destination, then their scan
     int32_t *s_rb = s_dest + R + 1;    // [E+1] row blocks per expert, then their scan
-    int32_t *s_free = s_rb + E + 2;
+    int32_t *s_grp = s_rb + E + 2;     // [R+1] fence groups per destination, then their scan
+    int32_t *s_free = s_grp + R + 1;
     MOE_TT_BEGIN();
     const bool seg_lds = plan_seg_in_lds(E, R), hist_lds = plan_hist_in_lds(nPB, E);
     int32_t *segc = a.seg_cnt, *segb = a.seg_begin, *hist = a.blk_base, *nfl = a.flag_base;
@@ -154,10 +155,16 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
         }
     }
     __syncthreads();
+    // fence groups of the per-destination mode: all flags of a destination, or group_size at a time
+    for (int r = tid; r < R; r += kThreads)
+        s_grp[r] = a.group_size > 0 ? (s_dest[r] + a.group_size - 1) / a.group_size : 1;
+    __syncthreads();
     if (wave == 0) {
         const int total = wave_exclusive_scan(s_dest, s_dest, R, 1, 0);
+        const int groups = wave_exclusive_scan(s_grp, s_grp, R, 1, 0);
         if (lane == 0) {
             s_dest[R] = total;
+            s_grp[R] = groups;
             a.ctrl->n_flags = (u32)total;
         }
     }
@@ -168,7 +175,10 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
     if (seg_lds)
         for (int q = tid; q < E * R; q += kThreads) a.seg_begin[q] = segb[q];
     for (int q = tid; q < E * R; q += kThreads) a.flag_base[q] = nfl[q] + s_dest[q / E];
-    for (int r = tid; r <= R; r += kThreads) a.dest_flag_begin[r] = s_dest[r];
+    for (int r = tid; r <= R; r += kThreads) {
+        a.dest_flag_begin[r] = s_dest[r];
+        a.dest_group_begin[r] = s_grp[r];
+    }
     __syncthreads();
     MOE_TT(a.ctrl, 38);
 }

@@ -127,7 +127,8 @@ __device__ __forceinline__ void mark_global(KArgs &a) {
     a.seg_begin = as_global(a.seg_begin);
     a.flag_base = as_global(a.flag_base);
     a.dest_flag_begin = as_global(a.dest_flag_begin);
-    a.dest_counter = as_global(a.dest_counter);
+    a.dest_group_begin = as_global(a.dest_group_begin);
+    a.group_counter = as_global(a.group_counter);
     a.rb_base = as_global(a.rb_base);
     a.rb_expert = as_global(a.rb_expert);
     a.h_ready = as_global(a.h_ready);
@@ -194,10 +195,12 @@ __device__ __forceinline__ void g1_tile(const KArgs &a, const TileInfo &ti, char
 //   PER_TILE: for every publish tile in turn: write it, barrier, release fence, flag
 //             (the coupled PUT -> FENCE -> SIGNAL of section 2.3).
 //   PER_DEST: write the whole compute tile, one release so the rows may be counted,
-//             add the publish tiles to their destination's counter (Algorithm 1,
-//             phase 1).  Whoever completes a destination's count is its leader: one
-//             fence at the requested scope, then all flags of that destination, stored
-//             by a whole wavefront (phase 2; lane-parallel signals as in appendix B).
+//             add the publish tiles to the counter of their fence group (Algorithm 1,
+//             phase 1; a group is all flags of a destination, or group_size consecutive
+//             ones: the granularity knob of section 4.1).  Whoever completes a group's
+//             count is its leader: one fence at the requested scope, then all flags of
+//             the group, stored by a whole wavefront (phase 2; lane-parallel signals as
+//             in appendix B).
 template <class P>
 __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
     using ET = typename P::ET;
@@ -275,29 +278,49 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
             fence_release(0);  // the rows of this tile may now be counted
             u64 n_fence = 0, n_flag = 0;
             for (int base = 0; base < nseg; base += 64) {
+                // lane i: the cbn flags [f0, f0 + cbn) of publish row-tile i; they lie in one
+                // destination and in one or more of its fence groups
                 const int i = base + lane;
-                bool lead = false;
-                int dst = 0;
-                if (i < nseg) {
-                    dst = s_dest[s_seg[i]];
-                    const u32 expect = (u32)(a.dest_flag_begin[dst + 1] - a.dest_flag_begin[dst]);
-                    const u32 old = atomicAdd(&a.dest_counter[dst], (u32)cbn);
-                    lead = (old + (u32)cbn == expect);
+                const bool active = i < nseg;
+                int f0 = 0, fb = 0, fe = 0, gs = 1, g_first = 0, g_last = -1, gid0 = 0;
+                if (active) {
+                    const int r0 = s_seg[i];
+                    const int dst = s_dest[r0];
+                    fb = a.dest_flag_begin[dst];
+                    fe = a.dest_flag_begin[dst + 1];
+                    f0 = a.slot_flag[s_slot[r0]] + cb0;
+                    gs = a.group_size > 0 ? a.group_size : fe - fb;
+                    g_first = (f0 - fb) / gs;
+                    g_last = (f0 + cbn - 1 - fb) / gs;
+                    gid0 = a.dest_group_begin[dst];
                 }
-                u64 m = __ballot(lead);
-                while (m) {
-                    const int src = __ffsll((long long)m) - 1;
-                    m &= m - 1;
-                    const int dd = __shfl(dst, src, 64);
-                    // every tile counted for dd was released (device scope) by its writer before
-                    // it was counted
-                    fence_acquire_no_invalidate();
-                    fence_release(sys);  // the one fence of this destination
-                    const int f0 = a.dest_flag_begin[dd], f1 = a.dest_flag_begin[dd + 1];
-                    for (int fi = f0 + lane; fi < f1; fi += 64) st_relaxed(&a.flags[fi], a.epoch, sys);
-                    if (lane == 0) __hip_atomic_store(&a.dest_counter[dd], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    n_fence += 1;
-                    n_flag += (u64)(f1 - f0);
+                for (int j = 0;; ++j) {
+                    const bool has = active && g_first + j <= g_last;
+                    if (__ballot(has) == 0ull) break;
+                    bool lead = false;
+                    const int gl = g_first + j;
+                    const int gbeg = fb + gl * gs, gend = min(gbeg + gs, fe);
+                    const int gid = gid0 + gl;
+                    if (has) {
+                        const u32 cnt = (u32)(min(f0 + cbn, gend) - max(f0, gbeg));
+                        const u32 old = atomicAdd(&a.group_counter[gid], cnt);
+                        lead = (old + cnt == (u32)(gend - gbeg));
+                    }
+                    u64 m = __ballot(lead);
+                    while (m) {
+                        const int src = __ffsll((long long)m) - 1;
+                        m &= m - 1;
+                        const int gb = __shfl(gbeg, src, 64), ge = __shfl(gend, src, 64), gi = __shfl(gid, src, 64);
+                        // every tile counted for this group was released (device scope) by its
+                        // writer before it was counted
+                        fence_acquire_no_invalidate();
+                        fence_release(sys);  // the one fence of this group
+                        for (int fi = gb + lane; fi < ge; fi += 64) st_relaxed(&a.flags[fi], a.epoch, sys);
+                        if (lane == 0)
+                            __hip_atomic_store(&a.group_counter[gi], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        n_fence += 1;
+                        n_flag += (u64)(ge - gb);
+                    }
                 }
             }
             if (lane == 0) {

@@ -257,8 +257,8 @@ struct Plan {
     int kind;
     Tiling tl;
     // workspace byte offsets
-    size_t o_ctrl, o_blk_hist, o_seg_cnt, o_dest_counter, o_h_ready, zero_bytes;
-    size_t o_blk_base, o_seg_begin, o_flag_base, o_dest_flag_begin, o_rb_base, o_rb_expert, o_h, total;
+    size_t o_ctrl, o_blk_hist, o_seg_cnt, o_group_counter, o_h_ready, zero_bytes;
+    size_t o_blk_base, o_seg_begin, o_flag_base, o_dest_flag_begin, o_dest_group_begin, o_rb_base, o_rb_expert, o_h, total;
 };
 
 static int make_plan(const moe_problem_t *p, Plan *pl) {
@@ -269,6 +269,7 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     if (p->signal_mode != MOE_SIGNAL_PER_TILE && p->signal_mode != MOE_SIGNAL_PER_DEST) return MOE_ERR_INVALID_ARG;
     if (p->fence_scope != MOE_SCOPE_AGENT && p->fence_scope != MOE_SCOPE_SYSTEM) return MOE_ERR_INVALID_ARG;
     if (p->tile_m < 0 || p->tile_n < 0) return MOE_ERR_INVALID_ARG;
+    if (p->group_size < 0 || (p->group_size != 0 && p->signal_mode != MOE_SIGNAL_PER_DEST)) return MOE_ERR_INVALID_ARG;
     if (p->E > kMaxExperts || p->k > 32 || p->R > kMaxDest) return MOE_ERR_UNSUPPORTED;
     if ((long long)p->T * p->k > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
     const int tm = p->tile_m ? p->tile_m : 128, tn = p->tile_n ? p->tile_n : 64;
@@ -323,13 +324,17 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     pl->o_ctrl = take(sizeof(Ctrl));
     pl->o_blk_hist = take((size_t)pl->nPB * p->E * 4);
     pl->o_seg_cnt = take((size_t)p->E * p->R * 4);
-    pl->o_dest_counter = take((size_t)p->R * 4);
+    // fence groups: one per destination, or at most flags / g + R of them
+    const size_t max_flags = ((size_t)(pl->N + tm - 1) / tm + (size_t)p->E * p->R) * pl->ncb;
+    const size_t max_groups = p->group_size > 0 ? max_flags / p->group_size + p->R : (size_t)p->R;
+    pl->o_group_counter = take(max_groups * 4);
     pl->o_h_ready = take((size_t)pl->maxRB_layout * 4);
     pl->zero_bytes = o;
     pl->o_blk_base = take((size_t)pl->nPB * p->E * 4);
     pl->o_seg_begin = take((size_t)p->E * p->R * 4);
     pl->o_flag_base = take((size_t)p->E * p->R * 4);
     pl->o_dest_flag_begin = take((size_t)(p->R + 1) * 4);
+    pl->o_dest_group_begin = take((size_t)(p->R + 1) * 4);
     pl->o_rb_base = take((size_t)(p->E + 1) * 4);
     pl->o_rb_expert = take((size_t)pl->maxRB_layout * 4);
     pl->o_h = take((size_t)pl->N * p->f * elem_size(p->dtype));
@@ -343,6 +348,7 @@ static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
     a->T = p.T; a->d = p.d; a->E = p.E; a->k = p.k; a->f = p.f; a->R = p.R;
     a->dtype = p.dtype; a->tile_m = pl.tile_m; a->tile_n = pl.tile_n;
     a->signal_mode = p.signal_mode; a->fence_scope = p.fence_scope; a->epoch = p.epoch;
+    a->group_size = p.group_size;
     a->N = pl.N; a->per_dest = pl.per_dest; a->ncb = pl.ncb;
     a->nPB = pl.nPB; a->nRT = pl.nRT; a->nCT = pl.nCT; a->comb_tokens = pl.comb_tokens;
     a->tl = pl.tl;
@@ -355,12 +361,13 @@ static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
         a->ctrl = (Ctrl *)(ws + pl.o_ctrl);
         a->blk_hist = (int32_t *)(ws + pl.o_blk_hist);
         a->seg_cnt = (int32_t *)(ws + pl.o_seg_cnt);
-        a->dest_counter = (u32 *)(ws + pl.o_dest_counter);
+        a->group_counter = (u32 *)(ws + pl.o_group_counter);
         a->h_ready = (u32 *)(ws + pl.o_h_ready);
         a->blk_base = (int32_t *)(ws + pl.o_blk_base);
         a->seg_begin = (int32_t *)(ws + pl.o_seg_begin);
         a->flag_base = (int32_t *)(ws + pl.o_flag_base);
         a->dest_flag_begin = (int32_t *)(ws + pl.o_dest_flag_begin);
+        a->dest_group_begin = (int32_t *)(ws + pl.o_dest_group_begin);
         a->rb_base = (int32_t *)(ws + pl.o_rb_base);
         a->rb_expert = (int32_t *)(ws + pl.o_rb_expert);
         a->h = ws + pl.o_h;
@@ -446,7 +453,7 @@ size_t moe_num_flags(const moe_problem_t *p) {
     Plan pl;
     if (make_plan(p, &pl) != MOE_OK) return 0;
     // a segment of c rows touches at most c/tile_m + 1 row blocks; there are E*R segments
-    return ((size_t)(pl.N + pl.tile_m - 1) / pl.tile_m + (size_t)p->E * p->R) * pl.ncb;
+    return ((size_t)(pl.N + pl.tile_m - 1) / pl.tile_m + (size_t)p->E * p->R) * pl.ncb;  // (make_plan sizes the group counters with the same bound)
 }
 
 int moe_workspace_init(const moe_problem_t *p, void *workspace, void *stream) {

@@ -75,5 +75,15 @@ def check_outputs(name, got, ref, ref_faithful, is_f32):
     return m
 
 
-def expected_fences(plan, signal_mode):
-    return plan["fences_per_tile"] if signal_mode == 0 else plan["fences_per_dest"]
+def expected_fences(plan, signal_mode, group_size=0):
+    """Release fences issued right before flag stores: one per publish tile in
+    the coupled mode; in the decoupled mode one per non-empty destination, or,
+    with a group size g, one per group of g flags of a destination:
+    sum over r of ceil(n_r / g) (section 4.1, granularity of Algorithm 1)."""
+    if signal_mode == 0:
+        return plan["fences_per_tile"]
+    if group_size == 0:
+        return plan["fences_per_dest"]
+    from oracle import accounting
+    n_r = np.diff(plan["dest_flag_begin"].astype(np.int64))
+    return int(sum(accounting.fence_count(int(n), group_size) for n in n_r if n > 0))

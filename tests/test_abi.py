@@ -51,12 +51,14 @@ def test_workspace_and_flag_sizes(B):
 
 
 @pytest.mark.parametrize("kw", [dict(k=9, E=8), dict(T=100, R=8), dict(T=0), dict(dtype=5), dict(signal_mode=3),
-                                dict(fence_scope=2), dict(tile_m=-1)])
+                                dict(fence_scope=2), dict(tile_m=-1), dict(group_size=-1, signal_mode=1),
+                                dict(group_size=4, signal_mode=0)])
 def test_invalid_problems_are_rejected_on_the_host(B, kw):
     base = dict(T=256, d=512, E=8, k=2, f=1024, R=2, dtype=1)
     base.update(kw)
     p = B.MoeProblem(base["T"], base["d"], base["E"], base["k"], base["f"], base["R"], base["dtype"],
-                     base.get("tile_m", 0), 0, base.get("signal_mode", 0), base.get("fence_scope", 0), 1)
+                     base.get("tile_m", 0), 0, base.get("signal_mode", 0), base.get("fence_scope", 0), 1,
+                     base.get("group_size", 0))
     assert B.moe_workspace_bytes(p) == 0 and B.moe_num_flags(p) == 0
     lib = ctypes.CDLL(LIB)
     rc = lib.moe_route(ctypes.byref(p), None, None, None, None, None, None)

@@ -16,12 +16,13 @@ pytestmark = pytest.mark.gpu
 SAMPLES = {"cfg1": 256, "cfg2": 48, "cfg3": 48, "cfg4": 12, "cfg5": 24, "cfg6": 24}
 
 
-def _run(name, signal_mode, fence_scope, inp=None, buf=None, epoch=1):
+def _run(name, signal_mode, fence_scope, inp=None, buf=None, epoch=1, group_size=0):
     from paper_2605_00686_amd import binding as B
     inp = inp or W.make_inputs(name)
     cfg = inp["cfg"]
     p = B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
-                  tile_n=cfg["tile_n"], signal_mode=signal_mode, fence_scope=fence_scope, epoch=epoch)
+                  tile_n=cfg["tile_n"], signal_mode=signal_mode, fence_scope=fence_scope, epoch=epoch,
+                  group_size=group_size)
     buf = buf or B.Buffers(p)
     dev = inp.setdefault("_dev", {n: (inp[n].cuda() if inp[n] is not None else None)
                                   for n in ("x", "Wg", "gate_bias", "W1", "W3", "W2")})
@@ -64,7 +65,7 @@ def _check(B, inp, p, buf, signal_mode, name, cache):
     nfl = plan["n_flags"]
     flags = buf.flags.cpu().numpy().view(np.uint32)
     assert nfl <= flags.size and np.all(flags[:nfl] == p.epoch)
-    assert stats[0] == parity.expected_fences(plan, signal_mode)
+    assert stats[0] == parity.expected_fences(plan, signal_mode, p.group_size)
     assert stats[1] == nfl and stats[2] == nfl
     # properties that hold at any size: nothing left unwritten, weights sum to one
     k, d = cfg["k"], cfg["d"]
@@ -88,7 +89,9 @@ def test_fullsize_parity(name):
     # the coupled mode on the same buffers (workspace reuse at full size)
     B, inp, p, buf = _run(name, 0, 0, inp=inp, buf=buf, epoch=2)
     _check(B, inp, p, buf, 0, name, cache)
-    if name == "cfg5":  # signaling stress: both scopes as well
+    if name == "cfg5":  # signaling stress: both scopes as well, and fence groups of 16 flags
         for epoch, (mode, scope) in enumerate([(1, 1), (0, 1)], start=3):
             B, inp, p, buf = _run(name, mode, scope, inp=inp, buf=buf, epoch=epoch)
             _check(B, inp, p, buf, mode, name, cache)
+        B, inp, p, buf = _run(name, 1, 0, inp=inp, epoch=5, group_size=16)  # (its own, larger workspace)
+        _check(B, inp, p, buf, 1, name, cache)

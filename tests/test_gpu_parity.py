@@ -21,14 +21,15 @@ def _dev(inp, names):
     return {n: (inp[n].cuda() if inp.get(n) is not None else None) for n in names}
 
 
-def _problem(B, cfg, signal_mode=1, fence_scope=0, epoch=1):
+def _problem(B, cfg, signal_mode=1, fence_scope=0, epoch=1, group_size=0):
     return B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
-                     tile_n=cfg["tile_n"], signal_mode=signal_mode, fence_scope=fence_scope, epoch=epoch)
+                     tile_n=cfg["tile_n"], signal_mode=signal_mode, fence_scope=fence_scope, epoch=epoch,
+                     group_size=group_size)
 
 
-def run_forward(B, inp, signal_mode, fence_scope, epoch=1, buf=None):
+def run_forward(B, inp, signal_mode, fence_scope, epoch=1, buf=None, group_size=0):
     cfg = inp["cfg"]
-    p = _problem(B, cfg, signal_mode, fence_scope, epoch)
+    p = _problem(B, cfg, signal_mode, fence_scope, epoch, group_size)
     buf = buf or B.Buffers(p)
     d = _dev(inp, ("x", "Wg", "gate_bias", "W1", "W3", "W2"))
     if cfg["prerouted"] is not None:
@@ -63,7 +64,8 @@ def check_against_oracle(B, inp, p, buf, signal_mode, ref=None):
     assert nfl <= B.moe_num_flags(p)
     flags = buf.flags.cpu().numpy().view(np.uint32)
     assert np.all(flags[:nfl] == p.epoch), "a published tile has no flag"
-    assert stats[0] == parity.expected_fences(plan, signal_mode), (stats, plan["fences_per_tile"], plan["fences_per_dest"])
+    assert stats[0] == parity.expected_fences(plan, signal_mode, p.group_size), \
+        (stats, plan["fences_per_tile"], plan["fences_per_dest"], p.group_size)
     assert stats[1] == nfl and stats[2] == nfl
     # floating point
     is_f32 = cfg["dtype"] == "f32"
@@ -87,6 +89,23 @@ def test_megakernel_parity(name, signal_mode):
     inp = W.make_inputs(name)
     p, buf = run_forward(B, inp, signal_mode, 0)
     check_against_oracle(B, inp, p, buf, signal_mode)
+
+
+@pytest.mark.parametrize("name", ["mini_bf16", "mini_decode", "mini_pre"])
+def test_megakernel_fence_group_size(name):
+    """Decoupled signaling at several granularities (section 4.1: one fence per
+    group of g signals).  Same buffers for every g, rising epochs: outputs and
+    flags as always, fences = sum over destinations of ceil(flags / g)."""
+    B = _binding()
+    inp = W.make_inputs(name)
+    ref, buf = None, None
+    for epoch, g in enumerate([1, 3, 8, 64, 100000, 0], start=2):
+        print(f"case {name} group_size {g}", flush=True)
+        # the workspace depends on g (number of group counters): keep the largest, which is g = 1, from the start
+        if buf is None:
+            buf = B.Buffers(_problem(B, inp["cfg"], 1, 0, 1, group_size=1))
+        p, buf = run_forward(B, inp, 1, 0, epoch=epoch, buf=buf, group_size=g)
+        ref = check_against_oracle(B, inp, p, buf, 1, ref)
 
 
 def test_megakernel_system_scope_and_reuse():
