@@ -192,8 +192,12 @@ __device__ __forceinline__ bool wait_ge(Ctrl *c, const u32 *p, u32 target) {
 }
 
 // phase bookkeeping for the in-kernel timeline (ticks since the first task)
-__device__ __forceinline__ void mark_phase_end(Ctrl *c, int phase) {
-    const u64 t0 = __hip_atomic_load(&c->t0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ u64 kernel_start_ticks(Ctrl *c) {
+    return __hip_atomic_load(&c->t0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// t0 = kernel_start_ticks(), read once per stage: it is final before any task is drawn, and
+// reading it here would put a trip to memory between two workgroup barriers of every task
+__device__ __forceinline__ void mark_phase_end(Ctrl *c, int phase, u64 t0) {
     atomicMax(&c->stats[8 + phase], now_ticks() - t0);
 }
 

@@ -17,10 +17,10 @@ struct Bf16Policy {
     static constexpr int SMEM_MAIN = C::SMEM_MAIN;
     // wavefronts per SIMD the kernel is built for: two workgroups per CU where their LDS fits
     static constexpr int MIN_WAVES = (2 * (C::SMEM_MAIN + 8 * 1024) <= 160 * 1024) ? 2 : 1;
-    template <bool GATED, class RowPtr>
+    template <bool GATED, class RowPtr, class Hook>
     static __device__ __forceinline__ void gemm(RowPtr rp, const ET *B0, const ET *B1, int ldb, int ncols, int K,
-                                                char *smem) {
-        gemm_tile_bf16<C, GATED>(rp, B0, B1, ldb, ncols, K, smem);
+                                                char *smem, Hook while_loading) {
+        gemm_tile_bf16<C, GATED>(rp, B0, B1, ldb, ncols, K, smem, while_loading);
     }
 };
 struct F32Policy {
@@ -29,10 +29,10 @@ struct F32Policy {
     static constexpr int C_STRIDE = TileF32::C_STRIDE;
     static constexpr int SMEM_MAIN = TileF32::SMEM_MAIN;
     static constexpr int MIN_WAVES = 1;
-    template <bool GATED, class RowPtr>
+    template <bool GATED, class RowPtr, class Hook>
     static __device__ __forceinline__ void gemm(RowPtr rp, const ET *B0, const ET *B1, int ldb, int ncols, int K,
-                                                char *smem) {
-        gemm_tile_f32<GATED>(rp, B0, B1, ldb, ncols, K, smem);
+                                                char *smem, Hook while_loading) {
+        gemm_tile_f32<GATED>(rp, B0, B1, ldb, ncols, K, smem, while_loading);
     }
 };
 // LDS after the GEMM region: per-row slot / destination, publish row-tile list
@@ -169,7 +169,7 @@ __device__ __forceinline__ void g1_tile(const KArgs &a, const TileInfo &ti, char
     };
     const size_t wofs = (size_t)ti.e * a.d * a.f + ti.n0;
     MOE_TT_BEGIN();
-    P::template gemm<true>(rowptr, (const ET *)a.W1 + wofs, (const ET *)a.W3 + wofs, a.f, ti.ncols, a.d, smem);
+    P::template gemm<true>(rowptr, (const ET *)a.W1 + wofs, (const ET *)a.W3 + wofs, a.f, ti.ncols, a.d, smem, [] {});
     after_gemm();
     MOE_TT(a.ctrl, 1);
     const int ppr = ti.ncols * (int)sizeof(ET) / 16;
@@ -201,9 +201,11 @@ __device__ __forceinline__ void g1_tile(const KArgs &a, const TileInfo &ti, char
 //             count is its leader: one fence at the requested scope, then all flags of
 //             the group, stored by a whole wavefront (phase 2; lane-parallel signals as
 //             in appendix B).
+// Row bookkeeping of a publish: slot and destination of every row of the compute
+// tile and the list of publish row-tiles, into LDS behind the GEMM's region (so it
+// can run while the GEMM's first loads are in flight).
 template <class P>
-__device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
-    using ET = typename P::ET;
+__device__ __forceinline__ void publish_prepare(const KArgs &a, const TileInfo &ti, char *smem) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int *s_slot = (int *)(smem + P::SMEM_MAIN);  // [BM] slot (= staging row) of local row r
     int *s_dest = s_slot + P::BM;                // [BM] destination of local row r
@@ -234,6 +236,17 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
     }
     __syncthreads();
     MOE_TT(a.ctrl, 11);
+}
+
+template <class P>
+__device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
+    using ET = typename P::ET;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int *s_slot = (const int *)(smem + P::SMEM_MAIN);  // filled by publish_prepare
+    const int *s_dest = s_slot + P::BM;
+    const int *s_seg = s_dest + P::BM;
+    const int *s_nseg = s_seg + P::BM + 1;
+    MOE_TT_BEGIN();
     const int nseg = *s_nseg;
     const int cbn = (ti.ncols + a.tile_n - 1) / a.tile_n;  // column blocks in this compute tile
     const int cb0 = ti.n0 / a.tile_n;
@@ -347,7 +360,7 @@ __device__ __forceinline__ void g2_tile(const KArgs &a, const TileInfo &ti, char
     auto rowptr = [&](int r) { return h + (size_t)(ti.row0 + min(r, ti.nrows - 1)) * a.f; };
     const ET *B0 = (const ET *)a.W2 + (size_t)ti.e * a.f * a.d + ti.n0;
     MOE_TT_BEGIN();
-    P::template gemm<false>(rowptr, B0, B0, a.d, ti.ncols, a.f, smem);
+    P::template gemm<false>(rowptr, B0, B0, a.d, ti.ncols, a.f, smem, [&] { publish_prepare<P>(a, ti, smem); });
     after_gemm();
     MOE_TT(a.ctrl, 7);
     publish_tile<P>(a, ti, smem);
@@ -384,6 +397,7 @@ __device__ __attribute__((noinline)) int tile_stage(KArgsAddr args, u32 smem_off
     StageLds *sl = (StageLds *)(smem + a.sched_lds_off);
     const Tables tb = decode_tables(a, smem, n_rb);
     const TileQueue tq = tile_queue(a, n_rb, q);
+    const u64 t0 = kernel_start_ticks(c);
     const int first = GATED ? 0 : tq.n1, last = GATED ? tq.n1 : tq.n1 + tq.n2;
     while (i >= first && i < last) {
         // the next entry is drawn after this tile's main loop and consumed at the end of the tile
@@ -411,7 +425,7 @@ __device__ __attribute__((noinline)) int tile_stage(KArgsAddr args, u32 smem_off
         }
         __syncthreads();
         if (tid == 0) {
-            mark_phase_end(c, GATED ? 3 : 4);
+            mark_phase_end(c, GATED ? 3 : 4, t0);
             sl->next = (int)next;
         }
         __syncthreads();
@@ -567,6 +581,7 @@ __device__ __forceinline__ void combine_stage(const KArgs &a, char *smem) {
     const int tid = threadIdx.x;
     Ctrl *c = a.ctrl;
     StageLds *sl = (StageLds *)(smem + a.sched_lds_off);
+    const u64 t0 = kernel_start_ticks(c);
     __syncthreads();
     if (tid == 0) sl->next = (int)atomicAdd(&c->comb_next, 1u);
     __syncthreads();
@@ -577,7 +592,7 @@ __device__ __forceinline__ void combine_stage(const KArgs &a, char *smem) {
         combine_task<ET, true>(a, t);
         __syncthreads();
         if (tid == 0) {
-            mark_phase_end(c, 5);
+            mark_phase_end(c, 5, t0);
             sl->next = (int)next;
         }
         __syncthreads();

@@ -71,9 +71,12 @@ __device__ __forceinline__ void wait_vmcnt() {
 //   ncols:     valid columns of each weight matrix from its first column (others: don't care)
 //   K:         multiple of 64
 // On return (after a barrier) the C tile is complete in smem; row stride C_STRIDE bytes.
-template <class C, bool GATED, class RowPtr>
+//   while_loading(): called by every thread once the first stages' loads are in flight, for
+//              work of the caller that fits into that trip to memory (it may use barriers and
+//              LDS beyond SMEM_MAIN)
+template <class C, bool GATED, class RowPtr, class Hook>
 __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1, int ldb, int ncols,
-                               int K, char *smem) {
+                               int K, char *smem, Hook while_loading) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / C::WN, wn = wave % C::WN;
     constexpr int HALF = C::BN / 2;
@@ -246,6 +249,9 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
     constexpr int PART0 = LPK < C::LPS ? LPK : C::LPS;
 #pragma unroll
     for (int i = 0; i < PART0; ++i) issue_one(fill_kt, fill_buf, i);
+    // (loads the caller issues here are younger than the stage loads: if they are still in
+    // flight at a vmcnt wait below, that wait only becomes stricter)
+    while_loading();
     wait_vmcnt<(C::NS - 2) * C::LPS + PART0>();
     __syncthreads();
     Frag f0, f1;

@@ -15,10 +15,11 @@ struct TileF32 {
     static constexpr int SMEM_MAIN = (STAGE > C_BYTES) ? STAGE : C_BYTES;
 };
 
-template <bool GATED, class RowPtr>
+template <bool GATED, class RowPtr, class Hook>
 __device__ void gemm_tile_f32(RowPtr rowptr, const float *B0, const float *B1, int ldb, int ncols, int K,
-                              char *smem) {
+                              char *smem, Hook while_loading) {
     using C = TileF32;
+    while_loading();  // (see gemm_tile_bf16; this loop has no loads in flight to hide it behind)
     const int tid = threadIdx.x;
     const int ty = tid >> 4, tx = tid & 15;
     float *As = (float *)smem;              // [BK][A_LD]

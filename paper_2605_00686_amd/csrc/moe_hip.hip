@@ -62,6 +62,7 @@ __device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
     const int tid = threadIdx.x;
     Ctrl *c = a.ctrl;
     StageLds *sl = (StageLds *)(smem + a.sched_lds_off);
+    const u64 t0 = kernel_start_ticks(c);
     __syncthreads();
     if (tid == 0) sl->next = (int)atomicAdd(&c->next_task, 1u);
     __syncthreads();
@@ -109,7 +110,7 @@ __device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
         }
         __syncthreads();
         if (tid == 0) {
-            mark_phase_end(c, phase);
+            mark_phase_end(c, phase, t0);
             sl->next = (int)atomicAdd(&c->next_task, 1u);
         }
         __syncthreads();
