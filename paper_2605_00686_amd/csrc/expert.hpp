@@ -477,6 +477,53 @@ struct Vec16<float> {
     }
 };
 
+// One token by one wavefront: out_row = sum_j wt[j] * rows[j], fp32 accumulation in
+// slot order, one rounding.  Each lane handles U 16-byte pieces of the row at a
+// time and loads 8/U slots of each before it accumulates them.
+template <typename ET, int U>
+__device__ __forceinline__ void combine_token(const char *rows, const float *wt, char *out_row, int k, int pieces,
+                                              size_t rstride, int lane) {
+    using V = Vec16<ET>;
+    constexpr int KB = 8 / U;
+    for (int c0 = lane; c0 < pieces; c0 += 64 * U) {
+        float acc[U][V::N];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int i = 0; i < V::N; ++i) acc[u][i] = 0.f;
+        for (int j0 = 0; j0 < k; j0 += KB) {
+            uint4 v[U][KB];
+#pragma unroll
+            for (int jj = 0; jj < KB; ++jj)
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int c = c0 + 64 * u;
+                    if (j0 + jj < k && c < pieces) v[u][jj] = *(const uint4 *)(rows + (size_t)(j0 + jj) * rstride + (size_t)c * 16);
+                }
+#pragma unroll
+            for (int jj = 0; jj < KB; ++jj) {
+                if (j0 + jj < k) {
+                    const float wj = wt[j0 + jj];
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        if (c0 + 64 * u < pieces) {
+                            float f[V::N];
+                            V::unpack(v[u][jj], f);
+#pragma unroll
+                            for (int i = 0; i < V::N; ++i) acc[u][i] = fmaf(wj, f[i], acc[u][i]);
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + 64 * u;
+            if (c < pieces) V::store(out_row + (size_t)c * 16, acc[u]);
+        }
+    }
+}
+
 // out[t] = sum_j w[t,j] * staging[t*k+j] for the tokens of one task.  WAIT:
 // spin (bounded) until the flags covering the task's rows carry this call's
 // epoch; otherwise check once and report.  Flags are read with relaxed atomic
@@ -528,49 +575,18 @@ __device__ __forceinline__ void combine_task(const KArgs &a, int task) {
     const size_t rstride = (size_t)a.d * sizeof(ET);
     for (int tt = wave; tt < nt; tt += 4) {
         const int t = t_first + tt;
+        const char *rows = staging + (size_t)t * k * rstride;
+        char *orow = (char *)a.out + (size_t)t * rstride;
         const float *wt = a.w + (size_t)t * k;
-        for (int c = lane; c < pieces; c += 64) {
-            float acc[V::N];
-#pragma unroll
-            for (int i = 0; i < V::N; ++i) acc[i] = 0.f;
-            const char *row = staging + (size_t)t * k * rstride + (size_t)c * 16;
-            int j = 0;
-            for (; j + 8 <= k; j += 8) {
-                uint4 v[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) v[u] = *(const uint4 *)(row + (size_t)(j + u) * rstride);
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    float f[V::N];
-                    V::unpack(v[u], f);
-                    const float wj = wt[j + u];
-#pragma unroll
-                    for (int i = 0; i < V::N; ++i) acc[i] = fmaf(wj, f[i], acc[i]);
-                }
-            }
-            for (; j + 2 <= k; j += 2) {
-                const uint4 v0 = *(const uint4 *)(row + (size_t)j * rstride);
-                const uint4 v1 = *(const uint4 *)(row + (size_t)(j + 1) * rstride);
-                float f0[V::N], f1[V::N];
-                V::unpack(v0, f0);
-                V::unpack(v1, f1);
-                const float w0 = wt[j], w1 = wt[j + 1];
-#pragma unroll
-                for (int i = 0; i < V::N; ++i) {
-                    acc[i] = fmaf(w0, f0[i], acc[i]);
-                    acc[i] = fmaf(w1, f1[i], acc[i]);
-                }
-            }
-            for (; j < k; ++j) {
-                const uint4 v0 = *(const uint4 *)(row + (size_t)j * rstride);
-                float f0[V::N];
-                V::unpack(v0, f0);
-                const float w0 = wt[j];
-#pragma unroll
-                for (int i = 0; i < V::N; ++i) acc[i] = fmaf(w0, f0[i], acc[i]);
-            }
-            V::store((char *)a.out + (size_t)t * rstride + (size_t)c * 16, acc);
-        }
+        // eight 16-byte loads in flight per lane whatever k is
+        if (k == 1)
+            combine_token<ET, 8>(rows, wt, orow, k, pieces, rstride, lane);
+        else if (k <= 2)
+            combine_token<ET, 4>(rows, wt, orow, k, pieces, rstride, lane);
+        else if (k <= 4)
+            combine_token<ET, 2>(rows, wt, orow, k, pieces, rstride, lane);
+        else
+            combine_token<ET, 1>(rows, wt, orow, k, pieces, rstride, lane);
     }
 }
 
