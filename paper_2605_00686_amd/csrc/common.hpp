@@ -59,6 +59,7 @@ struct KArgs {
     int N, per_dest, ncb;  // slots, tokens per destination, column blocks per row
     int nPB, nRT, nCT;     // permutation blocks, gate tasks, combine tasks
     int comb_tokens;       // tokens per combine task
+    int seg_from_blocks;   // destinations are whole permutation blocks: the plan derives seg_cnt from blk_hist
     Tiling tl;
     // front task ranges of the persistent scheduler: [route | plan | perm), then the tile
     // queues and the combine tasks; t_end bounds the useful number of workgroups

@@ -39,7 +39,8 @@ __device__ __forceinline__ int wave_exclusive_scan(const int32_t *src, int32_t *
     return carry;
 }
 
-// Single-workgroup task.  Reads blk_hist[nPB][E] and seg_cnt[E][R] (complete),
+// Single-workgroup task.  Reads blk_hist[nPB][E] and, unless it can be derived from it, seg_cnt[E][R]
+// (complete),
 // writes counts, offsets, blk_base, seg_begin, flag_base, dest_flag_begin, dest_group_begin,
 // rb_base, rb_expert, ctrl->n_rb, ctrl->n_flags.  The inputs are first copied
 // to LDS with coalesced loads; every scan then runs either one thread per
@@ -64,11 +65,22 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
         segb = segc + E * R;
         nfl = segb + E * R;  // [R][E]
         s_free = nfl + E * R;
-        for (int q = tid; q < E * R; q += kThreads) segc[q] = a.seg_cnt[q];
+        if (!a.seg_from_blocks)
+            for (int q = tid; q < E * R; q += kThreads) segc[q] = a.seg_cnt[q];
     }
     if (hist_lds) hist = s_free;
     for (int q = tid; q < nPB * E; q += kThreads) hist[q] = a.blk_hist[q];  // (blk_base <- blk_hist if not in LDS)
     __syncthreads();
+    if (a.seg_from_blocks) {  // a destination is a whole number of blocks: add up its blocks' histograms
+        const int bpd = a.per_dest / kPermBlock;
+        for (int q = tid; q < E * R; q += kThreads) {
+            const int e = q / R, r = q - e * R;
+            int c = 0;
+            for (int b = r * bpd; b < (r + 1) * bpd; ++b) c += hist[b * E + e];
+            segc[q] = c;
+        }
+        __syncthreads();
+    }
     MOE_TT(a.ctrl, 34);
     // per expert: rows per destination -> first row of each (e, r) segment and the total
     if (R <= 16) {

@@ -352,6 +352,7 @@ static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
     a->group_size = p.group_size;
     a->N = pl.N; a->per_dest = pl.per_dest; a->ncb = pl.ncb;
     a->nPB = pl.nPB; a->nRT = pl.nRT; a->nCT = pl.nCT; a->comb_tokens = pl.comb_tokens;
+    a->seg_from_blocks = (pl.per_dest % kPermBlock == 0) ? 1 : 0;
     a->tl = pl.tl;
     a->t_plan = pl.nRT;
     a->t_perm = a->t_plan + 1;
@@ -504,11 +505,11 @@ int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx,
     if ((rc = set_smem(k_plan, psmem))) return rc;
     // histogram (gate task without the gate), plan, permutation, row gather, clean-up
     if (p->dtype == MOE_DT_F32) {
-        hipLaunchKernelGGL(k_route<float>, dim3(pl.nRT), dim3(kThreads), 0, st, a, 1);
+        hipLaunchKernelGGL(k_route<float>, dim3(pl.nRT), dim3(kThreads), (size_t)p->E * 4, st, a, 1);
         hipLaunchKernelGGL(k_plan, dim3(1), dim3(kThreads), psmem, st, a);
         hipLaunchKernelGGL(k_perm<float>, dim3(pl.nPB), dim3(kThreads), (size_t)p->E * 8, st, a);
     } else {
-        hipLaunchKernelGGL(k_route<bf16_t>, dim3(pl.nRT), dim3(kThreads), 0, st, a, 1);
+        hipLaunchKernelGGL(k_route<bf16_t>, dim3(pl.nRT), dim3(kThreads), (size_t)p->E * 4, st, a, 1);
         hipLaunchKernelGGL(k_plan, dim3(1), dim3(kThreads), psmem, st, a);
         hipLaunchKernelGGL(k_perm<bf16_t>, dim3(pl.nPB), dim3(kThreads), (size_t)p->E * 8, st, a);
     }

@@ -245,58 +245,104 @@ __device__ __forceinline__ void route_task(const KArgs &a, int task, char *smem,
     const double *lg = (const double *)smem;
     const double NEG = -__builtin_huge_val();
 
-    for (int tl = wave; tl < kRouteTokens; tl += 4) {
-        const int t = t0 + tl;
-        if (t >= a.T) break;
-        int my_e = -1;
-        if (compute) {
-            double v0 = (lane < E) ? lg[tl * E + lane] : NEG;
-            double v1 = (lane + 64 < E) ? lg[tl * E + lane + 64] : NEG;
-            double v2 = (lane + 128 < E) ? lg[tl * E + lane + 128] : NEG;
-            double v3 = (lane + 192 < E) ? lg[tl * E + lane + 192] : NEG;
-            double my_v = 0.0;
-            for (int j = 0; j < k; ++j) {
-                double bv = v0;
-                int bi = lane;
-                argmax_merge(bv, bi, v1, lane + 64);
-                argmax_merge(bv, bi, v2, lane + 128);
-                argmax_merge(bv, bi, v3, lane + 192);
+    // Each wavefront selects for its four tokens (wave, wave + 4, ...) at once: the four
+    // shuffle chains are independent, so their latencies overlap.
+    constexpr int TPW = kRouteTokens / 4;
+    int my_e[TPW];
 #pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) {
-                    double ov = __shfl_xor(bv, off, 64);
-                    int oi = __shfl_xor(bi, off, 64);
-                    argmax_merge(bv, bi, ov, oi);
+    for (int i = 0; i < TPW; ++i) my_e[i] = -1;
+    if (compute) {
+        double v[TPW][4], my_v[TPW];
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            const int tl = wave + 4 * i;
+            my_v[i] = 0.0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[i][q] = (lane + 64 * q < E) ? lg[tl * E + lane + 64 * q] : NEG;
+        }
+        for (int j = 0; j < k; ++j) {
+            double bv[TPW];
+            int bi[TPW];
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                bv[i] = v[i][0];
+                bi[i] = lane;
+#pragma unroll
+                for (int q = 1; q < 4; ++q) argmax_merge(bv[i], bi[i], v[i][q], lane + 64 * q);
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) {
+                    const double ov = __shfl_xor(bv[i], off, 64);
+                    const int oi = __shfl_xor(bi[i], off, 64);
+                    argmax_merge(bv[i], bi[i], ov, oi);
                 }
-                if (bi == lane) v0 = NEG;
-                if (bi == lane + 64) v1 = NEG;
-                if (bi == lane + 128) v2 = NEG;
-                if (bi == lane + 192) v3 = NEG;
+            }
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (bi[i] == lane + 64 * q) v[i][q] = NEG;
                 if (lane == j) {
-                    my_v = bv;
-                    my_e = bi;
+                    my_v[i] = bv[i];
+                    my_e[i] = bi[i];
                 }
             }
-            // softmax over the k chosen logits
-            const double m = __shfl(my_v, 0, 64);
-            double ex = (lane < k) ? exp(my_v - m) : 0.0;
-            double s = ex;
+        }
+        // softmax over the k chosen logits
+        double ex[TPW], sum[TPW];
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
-            if (lane < k) {
-                a.idx[(size_t)t * k + lane] = my_e;
-                a.w[(size_t)t * k + lane] = (float)(ex / s);
-            }
-        } else if (lane < k) {
-            my_e = a.idx[(size_t)t * k + lane];
+        for (int i = 0; i < TPW; ++i) {
+            const double m = __shfl(my_v[i], 0, 64);
+            ex[i] = (lane < k) ? exp(my_v[i] - m) : 0.0;
+            sum[i] = ex[i];
         }
-        if (do_hist && lane < k) {
-            if (my_e < 0 || my_e >= E) {
-                set_error(a.ctrl, MOE_ERR_BAD_ROUTING);
-            } else {
-                atomicAdd(&a.blk_hist[(size_t)(t / kPermBlock) * E + my_e], 1);
-                atomicAdd(&a.seg_cnt[(size_t)my_e * a.R + t / a.per_dest], 1);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1)
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) sum[i] += __shfl_xor(sum[i], off, 64);
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            const int t = t0 + wave + 4 * i;
+            if (t < a.T && lane < k) {
+                a.idx[(size_t)t * k + lane] = my_e[i];
+                a.w[(size_t)t * k + lane] = (float)(ex[i] / sum[i]);
             }
         }
+    } else {
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            const int t = t0 + wave + 4 * i;
+            if (t < a.T && lane < k) my_e[i] = a.idx[(size_t)t * k + lane];
+        }
+    }
+    if (do_hist) {
+        // The task's 16 tokens lie in one permutation block: count them per expert in LDS
+        // (behind the logits; the staging buffers are free by now), then add the non-zero
+        // counts to the block's histogram: few, uncontended global atomics.  The
+        // per-destination counts come from the block histograms in the plan whenever
+        // destinations are whole blocks; else they are counted here, slot by slot.
+        int *cnt = (int *)(smem + (compute ? (size_t)kRouteTokens * E * 8 : 0));  // (no logits in LDS: E ints suffice)
+        for (int e = threadIdx.x; e < E; e += kThreads) cnt[e] = 0;
+        __syncthreads();
+        if (lane < k) {
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                const int t = t0 + wave + 4 * i;
+                if (t >= a.T) continue;
+                if (my_e[i] < 0 || my_e[i] >= E) {
+                    set_error(a.ctrl, MOE_ERR_BAD_ROUTING);
+                } else {
+                    atomicAdd(&cnt[my_e[i]], 1);
+                    if (!a.seg_from_blocks) atomicAdd(&a.seg_cnt[(size_t)my_e[i] * a.R + t / a.per_dest], 1);
+                }
+            }
+        }
+        __syncthreads();
+        int32_t *bh = a.blk_hist + (size_t)(t0 / kPermBlock) * E;
+        for (int e = threadIdx.x; e < E; e += kThreads)
+            if (cnt[e] != 0) atomicAdd(&bh[e], cnt[e]);
     }
     MOE_TT(a.ctrl, 33);
 }
