@@ -11,6 +11,9 @@ namespace moe {
 typedef unsigned long long u64;
 typedef uint32_t u32;
 typedef unsigned short bf16_t;  // raw bf16 bits
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) u32 u32x4_t;  // 16 bytes in registers
 
 constexpr int kThreads = 256;       // every kernel here runs 4 wavefronts per workgroup
 constexpr int kPermBlock = 64;      // tokens per permutation block (one bit each in a 64-bit mask)
@@ -32,11 +35,12 @@ struct Ctrl {
     u32 n_flags;     // publish tiles / flags in use
     u32 tile_next[8];  // per-XCD tile queues: next entry to hand out
     u32 comb_next;     // next combine task
-    u32 pad[7];
+    u32 wgt_done;      // gate-weight transposition tasks finished
+    u32 pad[6];
     u64 t0;          // wall-clock tick of the first task drawn
     u64 stats[MOE_NUM_STATS];
 #ifdef MOE_TILE_TIMING
-    u64 dbg[40];  // development build only: time spent in the parts of a tile, summed over tiles
+    u64 dbg[48];  // development build only: time spent in the parts of a tile, summed over tiles
 #endif
 };
 
@@ -61,9 +65,10 @@ struct KArgs {
     int comb_tokens;       // tokens per combine task
     int seg_from_blocks;   // destinations are whole permutation blocks: the plan derives seg_cnt from blk_hist
     Tiling tl;
-    // front task ranges of the persistent scheduler: [route | plan | perm), then the tile
-    // queues and the combine tasks; t_end bounds the useful number of workgroups
-    int t_plan, t_perm, t_g1, t_end;
+    // front task ranges of the persistent scheduler: [gate-weight transposition | route | plan |
+    // perm), then the tile queues and the combine tasks; t_end bounds the useful number of
+    // workgroups
+    int t_gate, t_plan, t_perm, t_g1, t_end;
     // caller tensors
     const void *x, *Wg;
     const float *bias;
@@ -91,6 +96,7 @@ struct KArgs {
     int32_t *rb_expert;        // [maxRB]
     u32 *h_ready;              // [maxRB] GEMM1 tiles finished per row block
     void *h;                   // [N][f]
+    void *WgT;                 // [E][d] transposed gate weights (bf16 problems with a gate), else NULL
     size_t zero_bytes;         // bytes from ctrl that must be zero between calls
     int tab_lds_off;           // megakernel: LDS offset of the cached decode tables, 0 = none
     int sched_lds_off;         // megakernel: LDS offset of the tile loop's broadcast slots (16 bytes)

@@ -55,7 +55,7 @@ __global__ __launch_bounds__(kThreads) void k_combine(KArgs a) {
 }
 
 // Front tasks of the megakernel from their counter, in this order:
-// [gate tasks | plan | permutation blocks].  Returns nonzero if a wait failed or
+// [gate-weight transposition tiles | gate tasks | plan | permutation blocks].  Returns nonzero if a wait failed or
 // the routing was found invalid.
 template <typename ET>
 __device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
@@ -67,14 +67,28 @@ __device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
     if (tid == 0) sl->next = (int)atomicAdd(&c->next_task, 1u);
     __syncthreads();
     int task = uniform(sl->next);
-    bool seen_plan = false, bad = false;
+    bool seen_plan = false, seen_wgt = false, bad = false;
     // (the next task is only drawn when this one is done: there are about as many gate tasks
     // as workgroups, and drawing ahead would give the first workgroups two each)
     while (task < a.t_g1) {
         int phase;
-        if (task < a.t_plan) {
+        if (task < a.t_gate) {
             phase = 0;
-            route_task<ET>(a, task, smem, true);
+            wgt_task(a, task, smem);
+            sync_stores();
+            if (tid == 0) {
+                fence_release(0);
+                atomicAdd(&c->wgt_done, 1u);
+            }
+        } else if (task < a.t_plan) {
+            phase = 0;
+            if (a.t_gate > 0 && !seen_wgt) {  // the transposed gate weights are complete
+                if (tid == 0) sl->ok = wait_ge(c, &c->wgt_done, (u32)a.t_gate) ? 1 : 0;
+                __syncthreads();
+                seen_wgt = true;
+                bad = bad || !sl->ok;
+            }
+            if (!bad) route_task<ET>(a, task - a.t_gate, smem, true);
             sync_stores();
             if (tid == 0) {
                 fence_release(0);
@@ -229,6 +243,9 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
                    c->dbg[12] / n2 / 100., c->dbg[13] / n2 / 100., c->dbg[10] / (n1 + n2) / 100.);
             printf("gate (us/task, thread 0): logits %.2f, top-k and histograms %.2f\n", c->dbg[32] / (double)a.nRT / 100.,
                    c->dbg[33] / (double)a.nRT / 100.);
+            printf("screened gate (us/task): screen %.2f, candidates %.2f, exact %.2f, select %.2f; fallbacks %llu\n",
+                   c->dbg[40] / (double)a.nRT / 100., c->dbg[41] / (double)a.nRT / 100., c->dbg[42] / (double)a.nRT / 100.,
+                   c->dbg[43] / (double)a.nRT / 100., c->dbg[44]);
             printf("plan starts at %.2f us; ", c->dbg[39] / 100.);
             printf("plan (us): stage %.2f, expert scans %.2f, block scan %.2f, flags %.2f, write-back %.2f\n", c->dbg[34] / 100.,
                    c->dbg[35] / 100., c->dbg[36] / 100., c->dbg[37] / 100., c->dbg[38] / 100.);
@@ -259,7 +276,7 @@ struct Plan {
     Tiling tl;
     // workspace byte offsets
     size_t o_ctrl, o_blk_hist, o_seg_cnt, o_group_counter, o_h_ready, zero_bytes;
-    size_t o_blk_base, o_seg_begin, o_flag_base, o_dest_flag_begin, o_dest_group_begin, o_rb_base, o_rb_expert, o_h, total;
+    size_t o_blk_base, o_seg_begin, o_flag_base, o_dest_flag_begin, o_dest_group_begin, o_rb_base, o_rb_expert, o_h, o_wgt, total;
 };
 
 static int make_plan(const moe_problem_t *p, Plan *pl) {
@@ -339,6 +356,8 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     pl->o_rb_base = take((size_t)(p->E + 1) * 4);
     pl->o_rb_expert = take((size_t)pl->maxRB_layout * 4);
     pl->o_h = take((size_t)pl->N * p->f * elem_size(p->dtype));
+    // transposed gate weights (bf16 problems; unused when the routing is an input)
+    pl->o_wgt = take(p->dtype == MOE_DT_BF16 ? (size_t)p->E * p->d * 2 : 0);
     pl->total = o;
     return MOE_OK;
 }
@@ -354,6 +373,7 @@ static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
     a->nPB = pl.nPB; a->nRT = pl.nRT; a->nCT = pl.nCT; a->comb_tokens = pl.comb_tokens;
     a->seg_from_blocks = (pl.per_dest % kPermBlock == 0) ? 1 : 0;
     a->tl = pl.tl;
+    a->t_gate = 0;  // the megakernel adds the transposition tasks when it has a gate to compute
     a->t_plan = pl.nRT;
     a->t_perm = a->t_plan + 1;
     a->t_g1 = a->t_perm + pl.nPB;
@@ -399,6 +419,7 @@ static int launch_mega(const Plan &pl, const KArgs &a_in, hipStream_t st) {
     size_t smem = tile_smem_bytes<P>();
     const size_t rsm = route_smem_bytes(pl.p.E, elem_size(pl.p.dtype));
     if (a_in.Wg && rsm > smem) smem = rsm;
+    if (a_in.WgT && screen_smem_bytes(pl.p.E) > smem) smem = screen_smem_bytes(pl.p.E);
     if (plan_smem(pl) > smem) smem = plan_smem(pl);
     // decode tables live behind everything else, for the life of the workgroup
     KArgs a = a_in;
@@ -542,6 +563,14 @@ int moe_megakernel_forward(const moe_problem_t *p, const void *x, const void *Wg
     a.idx = topk_idx; a.w = topk_w; a.counts = counts; a.offsets = offsets; a.perm = perm; a.inv_perm = inv_perm;
     a.slot_flag = slot_flag; a.staging = staging; a.flags = flags; a.out = out;
     a.stats = (u64 *)stats;
+    if (Wg && p->dtype == MOE_DT_BF16 && p->E >= 64) {
+        // bf16 gate: screen on the bf16 matrix cores, exact fp64 logits for the candidates only; this
+        // needs the gate weights transposed, which the first front tasks of the kernel write
+        a.WgT = (char *)workspace + pl.o_wgt;
+        const int ntt = wgt_tasks(p->d, p->E);
+        a.t_gate = ntt;
+        a.t_plan += ntt; a.t_perm += ntt; a.t_g1 += ntt; a.t_end += ntt;
+    }
     hipStream_t st = (hipStream_t)stream;
     switch (pl.kind) {
         case TK_F32: return launch_mega<F32Policy>(pl, a, st);

@@ -7,7 +7,6 @@
 namespace moe {
 
 typedef __attribute__((ext_vector_type(4))) double f64x4_t;
-typedef __attribute__((ext_vector_type(4))) u32 u32x4_t;  // 16 bytes in registers
 
 // How a gate task lays out its work.  The gate weights and the task's 16 rows
 // of x pass through LDS in chunks of KC reduction indices (weights: row stride
@@ -231,84 +230,412 @@ __device__ __forceinline__ void route_logits_dispatch(const KArgs &a, int t0, ch
         route_logits<ET, 4, 1>(a, t0, smem);
 }
 
+// ---- bf16 problems inside the megakernel: screen in bf16, decide in fp64 -----
+//
+// The fp64 matrix cores deliver 30-45 TFLOP/s, which makes the exact logits of
+// all E experts the longest part of a gate task by far.  Only the k largest
+// matter, so the task first computes every logit approximately on the bf16
+// matrix cores together with a rigorous bound on its error, keeps the experts
+// that could be among the k largest, and computes exact fp64 logits for those
+// few only.  The result is identical to selecting on exact logits of all
+// experts:
+//   approximate  L~[t,e] = sum_i x*w (fp32 accumulation of exact products) + bias
+//   bound        eps[t,e] >= |L~ - L|, from A[t,e] = sum_i |x|*|w| (second MFMA on the
+//                magnitudes): every one of the d additions rounds (or truncates) by at
+//                most 2^-23 of a partial sum that is at most A, so |L~ - L| <= d * 2^-23 * A
+//                and twice that is taken, plus the rounding of the bias addition
+//   threshold    tau[t] = the k-th largest of (L~ - eps): at least k experts have an exact
+//                logit >= tau
+//   candidates   {e : L~ + eps >= tau}: every expert whose exact logit reaches the k-th
+//                largest exact logit is among them, ties included
+// Both MFMA operands must be contiguous along the reduction: x is, the gate
+// weights are not, so the front of the kernel first writes their transpose
+// WgT[E][d] into the workspace (wgt_task).  If a token ever has more than 64
+// candidates (logits closer together than their error bound, e.g. all equal)
+// the task falls back to exact logits for all experts.
+
+constexpr int kWgtTile = 64;  // transposition tile: 64 reduction indices x 64 experts
+__host__ __device__ inline int wgt_tasks(int d, int E) { return (d / kWgtTile) * ((E + kWgtTile - 1) / kWgtTile); }
+
+// WgT[e][k0 .. k0+64) = Wg[k0 .. k0+64)[e] for 64 experts, through LDS.
+__device__ __forceinline__ void wgt_task(const KArgs &a, int task, char *smem) {
+    const int tid = threadIdx.x;
+    const int E = a.E, d = a.d;
+    const int ebn = (E + kWgtTile - 1) / kWgtTile;
+    const int k0 = (task / ebn) * kWgtTile, e0 = (task % ebn) * kWgtTile;
+    constexpr int LD = kWgtTile + 2;  // LDS row length in elements (odd number of dwords: column reads spread over banks)
+    bf16_t *tile = (bf16_t *)smem;    // [64 k][LD]
+    const bf16_t *Wg = (const bf16_t *)a.Wg;
+    bf16_t *WgT = (bf16_t *)a.WgT;
+    for (int q = tid; q < kWgtTile * kWgtTile; q += kThreads) {
+        const int kk = q / kWgtTile, ee = q % kWgtTile;
+        tile[kk * LD + ee] = (e0 + ee < E) ? Wg[(size_t)(k0 + kk) * E + e0 + ee] : (bf16_t)0;
+    }
+    __syncthreads();
+    for (int q = tid; q < kWgtTile * kWgtTile / 2; q += kThreads) {  // two reduction indices per store
+        const int ee = q / (kWgtTile / 2), kk = (q % (kWgtTile / 2)) * 2;
+        if (e0 + ee < E)
+            *(u32 *)(WgT + (size_t)(e0 + ee) * d + k0 + kk) = (u32)tile[kk * LD + ee] | ((u32)tile[(kk + 1) * LD + ee] << 16);
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ u32 float_key(float f) {  // order-preserving map of floats to unsigned integers
+    const u32 u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+constexpr int kMaxCand = 64;
+// LDS of the screened gate: approximate logits and bounds, candidate lists, exact logits, the selection
+__host__ __device__ inline size_t screen_smem_bytes(int E) {
+    return (size_t)kRouteTokens * E * 8 + (size_t)kRouteTokens * kMaxCand * 12 + (size_t)kRouteTokens * 32 * 12 + 64;
+}
+
+// Returns true if the selection was made (my_e[i] = expert of output position `lane` of the
+// wavefront's token i, for lanes < k; idx and w written), false if the task must fall back to
+// exact logits of all experts (nothing written).
+template <int NBW>
+__device__ __forceinline__ bool route_screened(const KArgs &a, int t0, char *smem, int (&my_e)[kRouteTokens / 4]) {
+    constexpr int TPW = kRouteTokens / 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int E = a.E, d = a.d, k = a.k;
+    const int li = lane & 15, kq = lane >> 4;
+    float *Ls = (float *)smem;                                  // [16][E] approximate logits
+    float *As = Ls + kRouteTokens * E;                          // [16][E] error bounds
+    int *cand = (int *)(As + kRouteTokens * E);                 // [16][64] candidate experts
+    double *exact = (double *)(cand + kRouteTokens * kMaxCand); // [16][64] their exact logits
+    double *sel_v = exact + kRouteTokens * kMaxCand;            // [16][32] selected logits by output position
+    int *sel_e = (int *)(sel_v + kRouteTokens * 32);            // [16][32]
+    int *s_ncand = sel_e + kRouteTokens * 32;                   // [16] (0 = fall back)
+    const bf16_t *x = (const bf16_t *)a.x;
+    const bf16_t *WgT = (const bf16_t *)a.WgT;
+    MOE_TT_BEGIN();
+
+    // ---- screen: D[token][expert] on the bf16 matrix cores (16 x 16 x 32), values and magnitudes.
+    // Lane l feeds token (or expert) l % 16 and reduction indices 8 * (l / 16) .. + 7 of a chunk of 32.
+    {
+        const int tok = min(t0 + li, a.T - 1);
+        const bf16_t *xrow = x + (size_t)tok * d + 8 * kq;
+        const bf16_t *wrow[NBW];
+#pragma unroll
+        for (int b = 0; b < NBW; ++b) {
+            const int e = min((wave + 4 * b) * 16 + li, E - 1);
+            wrow[b] = WgT + (size_t)e * d + 8 * kq;
+        }
+        f32x4_t acc[NBW], mag[NBW];
+#pragma unroll
+        for (int b = 0; b < NBW; ++b) {
+            acc[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            mag[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        }
+        const u32x4_t absmask = u32x4_t{0x7fff7fffu, 0x7fff7fffu, 0x7fff7fffu, 0x7fff7fffu};
+        // U chunks of 32 per step; the loads of the next step are issued before this step's
+        // multiplications: the loop does almost no arithmetic per byte, so what counts is how many
+        // loads are in flight all the time
+        constexpr int U = NBW <= 2 ? 8 : 4;
+        const int nchunk = d / 32;
+        struct Batch {
+            u32x4_t xv[U], wv[U][NBW];
+        };
+        auto fetch = [&](int c0, Batch &r) __attribute__((always_inline)) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = min(c0 + u, nchunk - 1);  // past the end: repeat the last chunk, masked in mul()
+                r.xv[u] = *(const u32x4_t *)(xrow + c * 32);
+#pragma unroll
+                for (int b = 0; b < NBW; ++b) r.wv[u][b] = *(const u32x4_t *)(wrow[b] + c * 32);
+            }
+        };
+        auto mul = [&](int c0, const Batch &r) __attribute__((always_inline)) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const u32 live = (c0 + u < nchunk) ? ~0u : 0u;
+                const u32x4_t xl = r.xv[u] & u32x4_t{live, live, live, live};
+                const u32x4_t xa = xl & absmask;
+#pragma unroll
+                for (int b = 0; b < NBW; ++b) {
+                    const u32x4_t wa = r.wv[u][b] & absmask;
+                    acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xl),
+                                                                     __builtin_bit_cast(bf16x8_t, r.wv[u][b]), acc[b], 0, 0, 0);
+                    mag[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, xa),
+                                                                     __builtin_bit_cast(bf16x8_t, wa), mag[b], 0, 0, 0);
+                }
+            }
+        };
+        Batch r0, r1;
+        fetch(0, r0);
+        for (int c0 = 0; c0 < nchunk; c0 += 2 * U) {
+            fetch(c0 + U, r1);
+            mul(c0, r0);
+            fetch(c0 + 2 * U, r0);
+            mul(c0 + U, r1);
+        }
+        // D layout: lane l, register v -> token 4 * (l / 16) + v, expert (block) l % 16
+        const float scale = (float)(d + 64) * (1.0f / 4194304.0f);  // (d + 64) * 2^-22
+#pragma unroll
+        for (int b = 0; b < NBW; ++b) {
+            const int e = (wave + 4 * b) * 16 + li;
+            if (e < E) {
+                const float bias = a.bias ? a.bias[e] : 0.f;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int t = 4 * kq + v;
+                    const float l = acc[b][v] + bias;
+                    Ls[t * E + e] = l;
+                    As[t * E + e] = 1.01f * (mag[b][v] * scale + (fabsf(l) + fabsf(bias)) * (1.0f / 4194304.0f)) + 1e-30f;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    MOE_TT(a.ctrl, 40);
+
+    // ---- threshold and candidates, one token per wavefront at a time
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int tl = wave + 4 * i;
+        u32 klo[4], khi[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int e = lane + 64 * q;
+            if (e < E) {
+                const float l = Ls[tl * E + e], eps = As[tl * E + e];
+                klo[q] = float_key(l - eps);
+                khi[q] = float_key(l + eps);
+            } else {
+                klo[q] = 0u;
+                khi[q] = 0u;
+            }
+        }
+        // the k-th largest lower bound: largest key K with at least k lower bounds >= K
+        u32 K = 0u;
+        for (int bit = 31; bit >= 0; --bit) {
+            const u32 trial = K | (1u << bit);
+            int cnt = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (64 * q < E) cnt += __popcll(__ballot(klo[q] >= trial));
+            if (cnt >= k) K = trial;
+        }
+        int before = 0, mine[4], n = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const bool in = (lane + 64 * q < E) && khi[q] >= K;
+            const u64 m = __ballot(in);
+            mine[q] = in ? before + __popcll(m & ((1ull << lane) - 1ull)) : -1;
+            before += __popcll(m);
+        }
+        n = before;
+        if (n <= kMaxCand) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (mine[q] >= 0) cand[tl * kMaxCand + mine[q]] = lane + 64 * q;
+        }
+        if (lane == 0) s_ncand[tl] = (n <= kMaxCand) ? n : 0;
+    }
+    __syncthreads();
+    bool ok = true;  // (tokens past T repeat token T-1: they fail only if it does)
+    for (int t = 0; t < kRouteTokens; ++t) ok = ok && s_ncand[t] > 0;
+    if (!ok) {
+#ifdef MOE_TILE_TIMING
+        if (tid == 0) atomicAdd(&a.ctrl->dbg[44], 1ull);
+#endif
+        __syncthreads();
+        return false;
+    }
+
+    MOE_TT(a.ctrl, 41);
+    // ---- exact fp64 logits of the candidates: 16 lanes per candidate, four candidates at a time
+    {
+        const int g = lane >> 4, j = lane & 15;
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            const int tl = wave + 4 * i;
+            const int tok = min(t0 + tl, a.T - 1);
+            const int n = s_ncand[tl];
+            const bf16_t *xr = x + (size_t)tok * d;
+            for (int base = 0; base < n; base += 4) {
+                const int ci = min(base + g, n - 1);
+                const int e = cand[tl * kMaxCand + ci];
+                const bf16_t *wr = WgT + (size_t)e * d;
+                // 16-byte pieces j, j + 16, ... of the two rows, eight pieces' loads in flight at a time;
+                // a bf16 x bf16 product is exact in fp32, the accumulation is in fp64, in four
+                // independent chains (a single one is bound by the latency of the fp64 adder)
+                double s4[4] = {0.0, 0.0, 0.0, 0.0};
+                constexpr int PB = 8;
+                for (int m0 = 8 * j; m0 < d; m0 += 128 * PB) {
+                    u32x4_t xv[PB], wv[PB];
+#pragma unroll
+                    for (int u = 0; u < PB; ++u) {
+                        const int m = m0 + 128 * u;
+                        if (m < d) {
+                            xv[u] = *(const u32x4_t *)(xr + m);
+                            wv[u] = *(const u32x4_t *)(wr + m);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < PB; ++u) {
+                        if (m0 + 128 * u < d) {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                const float p0 = __uint_as_float(xv[u][c] << 16) * __uint_as_float(wv[u][c] << 16);
+                                const float p1 = __uint_as_float(xv[u][c] & 0xffff0000u) * __uint_as_float(wv[u][c] & 0xffff0000u);
+                                s4[c] += (double)p0;
+                                s4[c] += (double)p1;
+                            }
+                        }
+                    }
+                }
+                double sum = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+#pragma unroll
+                for (int off = 8; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+                if (j == 0 && base + g < n) exact[tl * kMaxCand + base + g] = sum + (a.bias ? (double)a.bias[e] : 0.0);
+            }
+        }
+    }
+    __syncthreads();
+    MOE_TT(a.ctrl, 42);
+
+    // ---- select: the output position of a candidate is the number of candidates that beat it
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int tl = wave + 4 * i;
+        const int n = s_ncand[tl];
+        if (lane < n) {
+            const double v = exact[tl * kMaxCand + lane];
+            const int e = cand[tl * kMaxCand + lane];
+            int rank = 0;
+            for (int c = 0; c < n; ++c) {
+                const double ov = exact[tl * kMaxCand + c];
+                const int oe = cand[tl * kMaxCand + c];
+                rank += (ov > v || (ov == v && oe < e)) ? 1 : 0;
+            }
+            if (rank < k) {
+                sel_v[tl * 32 + rank] = v;
+                sel_e[tl * 32 + rank] = e;
+            }
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int tl = wave + 4 * i;
+        const int t = t0 + tl;
+        my_e[i] = -1;
+        const double m = sel_v[tl * 32];
+        const double ex = (lane < k) ? exp(sel_v[tl * 32 + min(lane, k - 1)] - m) : 0.0;
+        double sum = ex;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+        if (lane < k) {
+            my_e[i] = sel_e[tl * 32 + lane];
+            if (t < a.T) {
+                a.idx[(size_t)t * k + lane] = my_e[i];
+                a.w[(size_t)t * k + lane] = (float)(ex / sum);
+            }
+        }
+    }
+    __syncthreads();
+    MOE_TT(a.ctrl, 43);
+    return true;
+}
+
+// Exact logits of all experts in lg[16][E] (LDS) -> top-k by k rounds of a 64-lane butterfly
+// argmax on (value, index), softmax over the chosen k; each wavefront selects for its four
+// tokens (wave, wave + 4, ...) at once, so that the four shuffle chains overlap.
+__device__ __forceinline__ void select_full(const KArgs &a, int t0, const double *lg, int (&my_e)[kRouteTokens / 4]) {
+    constexpr int TPW = kRouteTokens / 4;
+    const int E = a.E, k = a.k;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const double NEG = -__builtin_huge_val();
+    double v[TPW][4], my_v[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int tl = wave + 4 * i;
+        my_v[i] = 0.0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[i][q] = (lane + 64 * q < E) ? lg[tl * E + lane + 64 * q] : NEG;
+    }
+    for (int j = 0; j < k; ++j) {
+        double bv[TPW];
+        int bi[TPW];
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            bv[i] = v[i][0];
+            bi[i] = lane;
+#pragma unroll
+            for (int q = 1; q < 4; ++q) argmax_merge(bv[i], bi[i], v[i][q], lane + 64 * q);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+                const double ov = __shfl_xor(bv[i], off, 64);
+                const int oi = __shfl_xor(bi[i], off, 64);
+                argmax_merge(bv[i], bi[i], ov, oi);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (bi[i] == lane + 64 * q) v[i][q] = NEG;
+            if (lane == j) {
+                my_v[i] = bv[i];
+                my_e[i] = bi[i];
+            }
+        }
+    }
+    // softmax over the k chosen logits
+    double ex[TPW], sum[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const double m = __shfl(my_v[i], 0, 64);
+        ex[i] = (lane < k) ? exp(my_v[i] - m) : 0.0;
+        sum[i] = ex[i];
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1)
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) sum[i] += __shfl_xor(sum[i], off, 64);
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int t = t0 + wave + 4 * i;
+        if (t < a.T && lane < k) {
+            a.idx[(size_t)t * k + lane] = my_e[i];
+            a.w[(size_t)t * k + lane] = (float)(ex[i] / sum[i]);
+        }
+    }
+}
+
+template <typename ET>
+__device__ __forceinline__ bool route_screened_dispatch(const KArgs &a, int t0, char *smem, int (&my_e)[kRouteTokens / 4]) {
+    if (sizeof(ET) != 2 || a.WgT == nullptr) return false;
+    const int nbw = ((a.E + 15) / 16 + 3) / 4;
+    if (nbw <= 1) return route_screened<1>(a, t0, smem, my_e);
+    if (nbw == 2) return route_screened<2>(a, t0, smem, my_e);
+    if (nbw == 3) return route_screened<3>(a, t0, smem, my_e);
+    return route_screened<4>(a, t0, smem, my_e);
+}
+
 // One gate task: tokens [task*16, task*16+16).  With a.Wg == NULL the routing
 // is an input and only the histograms are produced.
 template <typename ET>
 __device__ __forceinline__ void route_task(const KArgs &a, int task, char *smem, bool do_hist) {
+    constexpr int TPW = kRouteTokens / 4;
     const int t0 = task * kRouteTokens;
     const int E = a.E, k = a.k;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool compute = (a.Wg != nullptr);
-    MOE_TT_BEGIN();
-    if (compute) route_logits_dispatch<ET>(a, t0, smem);
-    MOE_TT(a.ctrl, 32);
-    const double *lg = (const double *)smem;
-    const double NEG = -__builtin_huge_val();
-
-    // Each wavefront selects for its four tokens (wave, wave + 4, ...) at once: the four
-    // shuffle chains are independent, so their latencies overlap.
-    constexpr int TPW = kRouteTokens / 4;
     int my_e[TPW];
 #pragma unroll
     for (int i = 0; i < TPW; ++i) my_e[i] = -1;
+    MOE_TT_BEGIN();
     if (compute) {
-        double v[TPW][4], my_v[TPW];
-#pragma unroll
-        for (int i = 0; i < TPW; ++i) {
-            const int tl = wave + 4 * i;
-            my_v[i] = 0.0;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) v[i][q] = (lane + 64 * q < E) ? lg[tl * E + lane + 64 * q] : NEG;
-        }
-        for (int j = 0; j < k; ++j) {
-            double bv[TPW];
-            int bi[TPW];
-#pragma unroll
-            for (int i = 0; i < TPW; ++i) {
-                bv[i] = v[i][0];
-                bi[i] = lane;
-#pragma unroll
-                for (int q = 1; q < 4; ++q) argmax_merge(bv[i], bi[i], v[i][q], lane + 64 * q);
-            }
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-#pragma unroll
-                for (int i = 0; i < TPW; ++i) {
-                    const double ov = __shfl_xor(bv[i], off, 64);
-                    const int oi = __shfl_xor(bi[i], off, 64);
-                    argmax_merge(bv[i], bi[i], ov, oi);
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < TPW; ++i) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    if (bi[i] == lane + 64 * q) v[i][q] = NEG;
-                if (lane == j) {
-                    my_v[i] = bv[i];
-                    my_e[i] = bi[i];
-                }
-            }
-        }
-        // softmax over the k chosen logits
-        double ex[TPW], sum[TPW];
-#pragma unroll
-        for (int i = 0; i < TPW; ++i) {
-            const double m = __shfl(my_v[i], 0, 64);
-            ex[i] = (lane < k) ? exp(my_v[i] - m) : 0.0;
-            sum[i] = ex[i];
-        }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1)
-#pragma unroll
-            for (int i = 0; i < TPW; ++i) sum[i] += __shfl_xor(sum[i], off, 64);
-#pragma unroll
-        for (int i = 0; i < TPW; ++i) {
-            const int t = t0 + wave + 4 * i;
-            if (t < a.T && lane < k) {
-                a.idx[(size_t)t * k + lane] = my_e[i];
-                a.w[(size_t)t * k + lane] = (float)(ex[i] / sum[i]);
-            }
+        if (!route_screened_dispatch<ET>(a, t0, smem, my_e)) {
+            route_logits_dispatch<ET>(a, t0, smem);
+            MOE_TT(a.ctrl, 32);
+            select_full(a, t0, (const double *)smem, my_e);
         }
     } else {
 #pragma unroll

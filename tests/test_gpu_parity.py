@@ -108,6 +108,26 @@ def test_megakernel_fence_group_size(name):
         ref = check_against_oracle(B, inp, p, buf, 1, ref)
 
 
+def test_megakernel_gate_many_experts_and_ties():
+    """Gate with E >= 64 (the path that screens in bf16 and decides on exact fp64 logits of the
+    candidates only).  Some rows of x are zero, so all 96 logits of those tokens are equal: more
+    candidates than that path keeps, which sends the task down the exact path for all experts;
+    the tie-break (lower expert first, equal weights) must come out as the oracle's."""
+    B = _binding()
+    cfg = dict(T=192, d=256, E=96, k=4, f=128, R=4, dtype="bf16", seed=21)
+    inp = W.make_inputs(cfg)
+    inp["x"][5] = 0
+    inp["x"][40:44] = 0
+    inp["x"][191] = 0
+    for mode in (1, 0):
+        print(f"case gate E=96 with ties, signal_mode {mode}", flush=True)
+        p, buf = run_forward(B, inp, mode, 0)
+        check_against_oracle(B, inp, p, buf, mode)
+    idx = buf.topk_idx.cpu().numpy()
+    assert idx[5].tolist() == [0, 1, 2, 3] and idx[191].tolist() == [0, 1, 2, 3]
+    np.testing.assert_allclose(buf.topk_w.cpu().numpy()[40:44], 0.25, rtol=1e-6)
+
+
 def test_megakernel_system_scope_and_reuse():
     """Same buffers, three calls in a row with rising epochs, both scopes and
     both modes: the workspace must come back clean each time."""
