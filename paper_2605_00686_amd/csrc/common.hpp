@@ -31,12 +31,13 @@ struct Ctrl {
     u32 perm_done;   // permutation blocks finished
     u32 exit_count;  // workgroups that left the kernel
     u32 error;       // first device status (moe_status_t as positive number), 0 = ok
-    u32 n_rb;        // row blocks in use (all experts)
+    u32 n_rb;        // (big) row blocks in use, all experts
     u32 n_flags;     // publish tiles / flags in use
     u32 tile_next[8];  // per-XCD tile queues: next entry to hand out
     u32 comb_next;     // next combine task
     u32 wgt_done;      // gate-weight transposition tasks finished
-    u32 pad[6];
+    u32 n_rbs;         // small row blocks in use (mixed tile heights), all experts
+    u32 pad[5];
     u64 t0;          // wall-clock tick of the first task drawn
     u64 stats[MOE_NUM_STATS];
 #ifdef MOE_TILE_TIMING
@@ -46,7 +47,8 @@ struct Ctrl {
 
 // GEMM tiling chosen on the host.
 struct Tiling {
-    int BM;     // rows of a compute tile (multiple of tile_m)
+    int BM;     // rows of a compute tile (multiple of tile_m); with mixed heights: of the big tile
+    int BMS;    // mixed heights: rows of the small tile that takes an expert's last rows when they fit, 0 = one height
     int BN1;    // h columns per GEMM1 tile
     int BN2;    // y columns per GEMM2 tile
     int NT1;    // ceil(f / BN1)
@@ -94,6 +96,8 @@ struct KArgs {
     u32 *group_counter;        // [fence groups] publish tiles written so far (PER_DEST)
     int32_t *rb_base;          // [E+1] first row block of expert e
     int32_t *rb_expert;        // [maxRB]
+    int32_t *rbs_base;         // [E+1] first small row block of expert e (each expert has at most one)
+    int32_t *rbs_expert;       // [E]
     u32 *h_ready;              // [maxRB] GEMM1 tiles finished per row block
     void *h;                   // [N][f]
     void *WgT;                 // [E][d] transposed gate weights (bf16 problems with a gate), else NULL

@@ -13,7 +13,7 @@ constexpr size_t kPlanSegLds = 48 * 1024, kPlanHistLds = 32 * 1024;
 __host__ __device__ inline bool plan_seg_in_lds(int E, int R) { return (size_t)3 * E * R * 4 <= kPlanSegLds; }
 __host__ __device__ inline bool plan_hist_in_lds(int nPB, int E) { return (size_t)nPB * E * 4 <= kPlanHistLds; }
 __host__ __device__ inline size_t plan_smem_bytes(int E, int R, int nPB) {
-    size_t n = (size_t)(3 * E + 2 * R + 10) * 4;
+    size_t n = (size_t)(4 * E + 2 * R + 12) * 4;
     if (plan_seg_in_lds(E, R)) n += (size_t)3 * E * R * 4;
     if (plan_hist_in_lds(nPB, E)) n += (size_t)nPB * E * 4;
     return n;
@@ -42,7 +42,7 @@ __device__ __forceinline__ int wave_exclusive_scan(const int32_t *src, int32_t *
 // Single-workgroup task.  Reads blk_hist[nPB][E] and, unless it can be derived from it, seg_cnt[E][R]
 // (complete),
 // writes counts, offsets, blk_base, seg_begin, flag_base, dest_flag_begin, dest_group_begin,
-// rb_base, rb_expert, ctrl->n_rb, ctrl->n_flags.  The inputs are first copied
+// rb_base, rb_expert, rbs_base, rbs_expert, ctrl->n_rb, ctrl->n_rbs, ctrl->n_flags.  The inputs are first copied
 // to LDS with coalesced loads; every scan then runs either one thread per
 // sequence (many short sequences) or one wavefront per sequence with a shuffle
 // scan (few long ones), so that nothing walks a long sequence serially.
@@ -54,7 +54,8 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
     int32_t *s_dest = s_off + E + 1;   // [R+1] flags per destination, then their scan
     int32_t *s_rb = s_dest + R + 1;    // [E+1] row blocks per expert, then their scan
     int32_t *s_grp = s_rb + E + 2;     // [R+1] fence groups per destination, then their scan
-    int32_t *s_free = s_grp + R + 1;
+    int32_t *s_rbs = s_grp + R + 1;    // [E+1] small row blocks per expert (0 or 1), then their scan
+    int32_t *s_free = s_rbs + E + 2;
     MOE_TT_BEGIN();
     const bool seg_lds = plan_seg_in_lds(E, R), hist_lds = plan_hist_in_lds(nPB, E);
     int32_t *segc = a.seg_cnt, *segb = a.seg_begin, *hist = a.blk_base, *nfl = a.flag_base;
@@ -100,28 +101,43 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
         }
     }
     __syncthreads();
-    // rows and row blocks: exclusive scans over the experts
-    for (int e = tid; e < E; e += kThreads) s_rb[e] = (s_cnt[e] + a.tl.BM - 1) >> lbm;
+    // row blocks per expert.  One height: ceil(rows / BM).  Mixed heights: big blocks, and the last
+    // rows of the expert in one small block when they fit into it.
+    for (int e = tid; e < E; e += kThreads) {
+        const int n = s_cnt[e];
+        if (a.tl.BMS == 0) {
+            s_rb[e] = (n + a.tl.BM - 1) >> lbm;
+            s_rbs[e] = 0;
+        } else {
+            const int rem = n & (a.tl.BM - 1);
+            s_rb[e] = (n >> lbm) + (rem > a.tl.BMS ? 1 : 0);
+            s_rbs[e] = (rem > 0 && rem <= a.tl.BMS) ? 1 : 0;
+        }
+    }
     __syncthreads();
     if (wave == 0) {
         const int rows = wave_exclusive_scan(s_cnt, s_off, E, 1, 0);
         const int rb = wave_exclusive_scan(s_rb, s_rb, E, 1, 0);
+        const int rbs = wave_exclusive_scan(s_rbs, s_rbs, E, 1, 0);
         if (lane == 0) {
             s_off[E] = rows;
             s_rb[E] = rb;
+            s_rbs[E] = rbs;
             a.ctrl->n_rb = (u32)rb;
+            a.ctrl->n_rbs = (u32)rbs;
         }
     }
     __syncthreads();
     for (int e = tid; e <= E; e += kThreads) {
         a.offsets[e] = s_off[e];
         a.rb_base[e] = s_rb[e];
+        a.rbs_base[e] = s_rbs[e];
         if (e < E) {
             a.counts[e] = s_cnt[e];
             for (int i = s_rb[e]; i < s_rb[e + 1]; ++i) a.rb_expert[i] = e;
+            if (s_rbs[e + 1] > s_rbs[e]) a.rbs_expert[s_rbs[e]] = e;
         }
     }
-    MOE_TT(a.ctrl, 35);
     // sorted position of each block's first slot of e: exclusive scan over blocks
     if (E >= 64) {
         for (int e = tid; e < E; e += kThreads) {

@@ -51,50 +51,74 @@ struct TileInfo {
     bool valid;
 };
 
-// The three small tables a tile decode reads; they point into LDS once a
-// workgroup has copied them there (after the plan), else into the workspace.
+// The small tables a tile decode reads; they point into LDS once a workgroup has
+// copied them there (after the plan), else into the workspace.
+//
+// Row blocks come in one height, or in two (mixed heights): big blocks of
+// Tiling::BM rows, and for an expert whose last rows fit into Tiling::BMS rows
+// one small block for them.  Square-ish tiles move the fewest bytes per flop
+// from L2 to LDS (the 128-row tile is bound by that traffic), so an expert gets
+// as many 256-row tiles as it can fill and the 128-row tile only for a short
+// tail, instead of padding the tail to 256 rows or cutting everything to 128.
+// The two kinds have separate block numbers, tables and tile code (SMALL).
 struct Tables {
-    const int32_t *offsets, *rb_base, *rb_expert;
-    int n_rb;
+    const int32_t *offsets, *rb_base, *rb_expert, *rbs_base, *rbs_expert;
+    int n_rb, n_rbs;
 };
 
-// The row blocks [0, n_rb) of all experts, in expert order, are cut into
-// kTileQueues contiguous shares, one per XCD.  The queue of a share lists its
-// GEMM1 tiles, then its GEMM2 tiles; workgroups draw from the queue of the XCD
-// they run on (and from the others once it is empty).  Tiles that read the same
-// weights or the same rows therefore meet in one L2 instead of fetching the
-// operand once per XCD, and a GEMM2 tile only depends on entries that come
-// before it in its own queue.
+// The row blocks [0, n) of one kind of all experts, in expert order, are cut
+// into kTileQueues contiguous shares, one per XCD.  The queue of an XCD lists
+// the GEMM1 tiles of its share of the big blocks, then of its share of the small
+// blocks, then the GEMM2 tiles in the same order; workgroups draw from the queue
+// of the XCD they run on (and from the others once it is empty).  Tiles that
+// read the same weights or the same rows therefore meet in one L2 instead of
+// fetching the operand once per XCD, and a GEMM2 tile only depends on entries
+// that come before it in its own queue.
 struct TileQueue {
-    int r0, r1;  // row blocks of this share
-    int n1, n2;  // GEMM1 / GEMM2 tiles
+    int r0, r1;   // big row blocks of this share
+    int s0, s1;   // small row blocks of this share
+    int n1b, n1s; // GEMM1 tiles, big / small
+    int n2b, n2s; // GEMM2 tiles, big / small
+    __device__ __forceinline__ int n1() const { return n1b + n1s; }
+    __device__ __forceinline__ int total() const { return n1b + n1s + n2b + n2s; }
 };
-__device__ __forceinline__ TileQueue tile_queue(const KArgs &a, int n_rb, int q) {
+__device__ __forceinline__ TileQueue tile_queue(const KArgs &a, int n_rb, int n_rbs, int q) {
     TileQueue tq;
     tq.r0 = (int)(((long long)n_rb * q) / kTileQueues);
     tq.r1 = (int)(((long long)n_rb * (q + 1)) / kTileQueues);
-    tq.n1 = (tq.r1 - tq.r0) * a.tl.NT1;
-    tq.n2 = (tq.r1 - tq.r0) * a.tl.NT2;
+    tq.s0 = (int)(((long long)n_rbs * q) / kTileQueues);
+    tq.s1 = (int)(((long long)n_rbs * (q + 1)) / kTileQueues);
+    tq.n1b = (tq.r1 - tq.r0) * a.tl.NT1;
+    tq.n1s = (tq.s1 - tq.s0) * a.tl.NT1;
+    tq.n2b = (tq.r1 - tq.r0) * a.tl.NT2;
+    tq.n2s = (tq.s1 - tq.s0) * a.tl.NT2;
     return tq;
 }
 
-// Entry i of one phase of a queue -> tile.  Inside the share, the tiles of one
-// expert are consecutive and the column tile varies slowest, so tiles running
-// at the same time share one weight column block and the expert's rows.
+// Entry i of one phase and kind of a queue -> tile.  Inside the share, the tiles
+// of one expert are consecutive and the column tile varies slowest, so tiles
+// running at the same time share one weight column block and the expert's rows.
+// ti.rb numbers big blocks from 0 and small blocks from n_rb (index into h_ready).
+template <bool SMALL>
 __device__ __forceinline__ TileInfo decode_tile(const KArgs &a, const Tables &tb, const TileQueue &tq, int i, int NT,
                                                 int BN, int total_cols) {
     TileInfo ti;
-    const int e = tb.rb_expert[tq.r0 + i / NT];
-    const int e_rb0 = tb.rb_base[e];
-    const int s0 = max(e_rb0, tq.r0), s1 = min(tb.rb_base[e + 1], tq.r1);  // the expert's row blocks in this share
+    const int32_t *base = SMALL ? tb.rbs_base : tb.rb_base;
+    const int q0 = SMALL ? tq.s0 : tq.r0, q1 = SMALL ? tq.s1 : tq.r1;
+    const int BMK = SMALL ? a.tl.BMS : a.tl.BM;
+    const int e = (SMALL ? tb.rbs_expert : tb.rb_expert)[q0 + i / NT];
+    const int e_rb0 = base[e];
+    const int s0 = max(e_rb0, q0), s1 = min(base[e + 1], q1);  // the expert's row blocks of this kind in this share
     const int nrb = s1 - s0;
-    const int loc = i - (s0 - tq.r0) * NT;
+    const int loc = i - (s0 - q0) * NT;
     const int ct = loc / nrb, rbl = loc % nrb;
+    const int rb = s0 + rbl;
     ti.e = e;
-    ti.rb = s0 + rbl;
-    ti.lrow0 = (ti.rb - e_rb0) * a.tl.BM;
+    ti.rb = SMALL ? tb.n_rb + rb : rb;
+    // the small block follows the expert's big blocks
+    ti.lrow0 = SMALL ? (tb.rb_base[e + 1] - tb.rb_base[e]) * a.tl.BM : (rb - e_rb0) * BMK;
     ti.row0 = tb.offsets[e] + ti.lrow0;
-    ti.nrows = min(a.tl.BM, tb.offsets[e + 1] - ti.row0);
+    ti.nrows = min(BMK, tb.offsets[e + 1] - ti.row0);
     ti.n0 = ct * BN;
     ti.ncols = min(BN, total_cols - ti.n0);
     ti.valid = true;
@@ -131,23 +155,30 @@ __device__ __forceinline__ void mark_global(KArgs &a) {
     a.group_counter = as_global(a.group_counter);
     a.rb_base = as_global(a.rb_base);
     a.rb_expert = as_global(a.rb_expert);
+    a.rbs_base = as_global(a.rbs_base);
+    a.rbs_expert = as_global(a.rbs_expert);
     a.h_ready = as_global(a.h_ready);
     a.h = as_global((char *)a.h);
 }
 
 // The decode tables: the copies a workgroup made in LDS after the plan (see the
 // megakernel), else the workspace arrays.
-__device__ __forceinline__ Tables decode_tables(const KArgs &a, char *smem, int n_rb) {
+__device__ __forceinline__ Tables decode_tables(const KArgs &a, char *smem, int n_rb, int n_rbs) {
     Tables tb;
     tb.n_rb = n_rb;
-    if (a.tab_lds_off > 0) {
+    tb.n_rbs = n_rbs;
+    if (a.tab_lds_off > 0) {  // layout: see the copy in the megakernel
         tb.offsets = (const int32_t *)(smem + a.tab_lds_off);
         tb.rb_base = tb.offsets + a.E + 1;
-        tb.rb_expert = tb.rb_base + a.E + 1;
+        tb.rbs_base = tb.rb_base + a.E + 1;
+        tb.rb_expert = tb.rbs_base + a.E + 1;
+        tb.rbs_expert = tb.rb_expert + n_rb;
     } else {
         tb.offsets = a.offsets;
         tb.rb_base = a.rb_base;
         tb.rb_expert = a.rb_expert;
+        tb.rbs_base = a.rbs_base;
+        tb.rbs_expert = a.rbs_expert;
     }
     return tb;
 }
@@ -383,22 +414,23 @@ struct StageLds {  // broadcast slots of a stage's task loop, in dynamic LDS at 
     int next, ok;
 };
 
-// GEMM1 (GATED) or GEMM2 entries of tile queue q, starting with entry `i` that
-// the caller has drawn; returns the first entry drawn that is not its own.
-
-template <class P, bool GATED>
-__device__ __attribute__((noinline)) int tile_stage(KArgsAddr args, u32 smem_off, int q, int n_rb, int i) {
+// GEMM1 (GATED) or GEMM2 entries, big or SMALL row blocks, of tile queue q, starting with
+// entry `i` that the caller has drawn; returns the first entry drawn that is not its own.
+template <class P, bool GATED, bool SMALL>
+__device__ __attribute__((noinline)) int tile_stage(KArgsAddr args, u32 smem_off, int q, int n_rb, int n_rbs, int i) {
     KArgs a = load_kernel_args(args);
     mark_global(a);
     char *smem = lds_at((u32)uniform((int)smem_off));
-    q = uniform(q), n_rb = uniform(n_rb), i = uniform(i);
+    q = uniform(q), n_rb = uniform(n_rb), n_rbs = uniform(n_rbs), i = uniform(i);
     const int tid = threadIdx.x;
     Ctrl *c = a.ctrl;
     StageLds *sl = (StageLds *)(smem + a.sched_lds_off);
-    const Tables tb = decode_tables(a, smem, n_rb);
-    const TileQueue tq = tile_queue(a, n_rb, q);
+    const Tables tb = decode_tables(a, smem, n_rb, n_rbs);
+    const TileQueue tq = tile_queue(a, n_rb, n_rbs, q);
     const u64 t0 = kernel_start_ticks(c);
-    const int first = GATED ? 0 : tq.n1, last = GATED ? tq.n1 : tq.n1 + tq.n2;
+    // queue layout: [GEMM1 big | GEMM1 small | GEMM2 big | GEMM2 small]
+    const int first = (GATED ? 0 : tq.n1()) + (SMALL ? (GATED ? tq.n1b : tq.n2b) : 0);
+    const int last = first + (GATED ? (SMALL ? tq.n1s : tq.n1b) : (SMALL ? tq.n2s : tq.n2b));
     while (i >= first && i < last) {
         // the next entry is drawn after this tile's main loop and consumed at the end of the tile
         u32 next = 0x7fffffffu;
@@ -407,12 +439,12 @@ __device__ __attribute__((noinline)) int tile_stage(KArgsAddr args, u32 smem_off
         };
         MOE_TT_BEGIN();
         if (GATED) {
-            const TileInfo ti = decode_tile(a, tb, tq, i, a.tl.NT1, P::BN1, a.f);
+            const TileInfo ti = decode_tile<SMALL>(a, tb, tq, i - first, a.tl.NT1, P::BN1, a.f);
             MOE_TT(c, 0);
             g1_tile<P>(a, ti, smem, draw);
             MOE_TT(c, 4);
         } else {
-            const TileInfo ti = decode_tile(a, tb, tq, i - tq.n1, a.tl.NT2, P::BN2, a.d);
+            const TileInfo ti = decode_tile<SMALL>(a, tb, tq, i - first, a.tl.NT2, P::BN2, a.d);
             // h rows are written once, by GEMM1 tiles that released them before counting themselves
             if (tid == 0) sl->ok = wait_ge<false>(c, &a.h_ready[ti.rb], (u32)a.tl.NT1) ? 1 : 0;
             __syncthreads();

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstring>
+#include <type_traits>
 
 #include "common.hpp"
 #include "dispatch.hpp"
@@ -149,9 +150,13 @@ __device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
 // hides the counter's latency.  The kernel body itself only strings the stage
 // functions together (see StageLds) and never hands out a reference to its argument
 // block.
-template <class P>
+// P: tile policy (of the big tile when row blocks have two heights), PS: policy of the small tile
+// (= P when there is one height).
+template <class P, class PS>
 __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) {
     using ET = typename P::ET;
+    constexpr bool MIXED = !std::is_same<P, PS>::value;
+    static_assert(P::MIN_WAVES == PS::MIN_WAVES, "one occupancy for both tile codes");
     extern __shared__ __align__(16) char smem[];
     __shared__ int s_task, s_ok, s_last;
     Ctrl *c = a.ctrl;
@@ -170,18 +175,23 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
     if (tid == 0) s_ok = (wait_ge(c, &c->plan_done, 1u) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
     __syncthreads();
     bad = bad || !s_ok;
-    int n_rb = 0;
+    int n_rb = 0, n_rbs = 0;
     if (!bad) {
         n_rb = (int)c->n_rb;
-        if (a.tab_lds_off > 0) {
+        n_rbs = (int)c->n_rbs;
+        if (a.tab_lds_off > 0) {  // [offsets | rb_base | rbs_base | rb_expert | rbs_expert]
             int32_t *t_off = (int32_t *)(smem + a.tab_lds_off);
             int32_t *t_rbb = t_off + a.E + 1;
-            int32_t *t_rbe = t_rbb + a.E + 1;
+            int32_t *t_rsb = t_rbb + a.E + 1;
+            int32_t *t_rbe = t_rsb + a.E + 1;
+            int32_t *t_rse = t_rbe + n_rb;
             for (int i = tid; i <= a.E; i += kThreads) {
                 t_off[i] = a.offsets[i];
                 t_rbb[i] = a.rb_base[i];
+                t_rsb[i] = a.rbs_base[i];
             }
             for (int i = tid; i < n_rb; i += kThreads) t_rbe[i] = a.rb_expert[i];
+            for (int i = tid; i < n_rbs; i += kThreads) t_rse[i] = a.rbs_expert[i];
         }
     }
     __syncthreads();
@@ -194,15 +204,18 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
         const int home = xcd_id() % kTileQueues;
         for (int s = 0; s < kTileQueues; ++s) {
             const int q = (home + s) % kTileQueues;
-            const TileQueue tq = tile_queue(a, n_rb, q);
-            const int n_entries = tq.n1 + tq.n2;
+            const TileQueue tq = tile_queue(a, n_rb, n_rbs, q);
+            const int n_entries = tq.total();
             if (n_entries == 0) continue;
             __syncthreads();
             if (tid == 0) s_task = (int)atomicAdd(&c->tile_next[q], 1u);
             __syncthreads();
             int i = s_task;
-            if (i < tq.n1) i = tile_stage<P, true>(kargs, lds_offset(smem), q, n_rb, i);
-            if (i < n_entries) i = tile_stage<P, false>(kargs, lds_offset(smem), q, n_rb, i);
+            const u32 lds = lds_offset(smem);
+            if (i < tq.n1b) i = tile_stage<P, true, false>(kargs, lds, q, n_rb, n_rbs, i);
+            if (MIXED && i >= tq.n1b && i < tq.n1()) i = tile_stage<PS, true, true>(kargs, lds, q, n_rb, n_rbs, i);
+            if (i >= tq.n1() && i < tq.n1() + tq.n2b) i = tile_stage<P, false, false>(kargs, lds, q, n_rb, n_rbs, i);
+            if (MIXED && i >= tq.n1() + tq.n2b && i < n_entries) i = tile_stage<PS, false, true>(kargs, lds, q, n_rb, n_rbs, i);
         }
 #ifdef MOE_TILE_TIMING
         if (tid == 0) {
@@ -267,7 +280,7 @@ static inline size_t align_up(size_t v, size_t al) { return (v + al - 1) / al * 
 
 static int elem_size(int dtype) { return dtype == MOE_DT_F32 ? 4 : 2; }
 
-enum TileKind { TK_F32 = 0, TK_L = 1, TK_M = 2, TK_S = 3 };
+enum TileKind { TK_F32 = 0, TK_LM = 1, TK_S = 3 };  // LM: 256-row tiles plus a 128-row tile for short tails
 
 struct Plan {
     moe_problem_t p;
@@ -276,7 +289,7 @@ struct Plan {
     Tiling tl;
     // workspace byte offsets
     size_t o_ctrl, o_blk_hist, o_seg_cnt, o_group_counter, o_h_ready, zero_bytes;
-    size_t o_blk_base, o_seg_begin, o_flag_base, o_dest_flag_begin, o_dest_group_begin, o_rb_base, o_rb_expert, o_h, o_wgt, total;
+    size_t o_blk_base, o_seg_begin, o_flag_base, o_dest_flag_begin, o_dest_group_begin, o_rb_base, o_rb_expert, o_rbs_base, o_rbs_expert, o_h, o_wgt, total;
 };
 
 static int make_plan(const moe_problem_t *p, Plan *pl) {
@@ -316,23 +329,20 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
         pl->tl.BN1 = TileF32::BN;
         pl->tl.BN2 = TileF32::BN;
     } else {
-        if (avg >= 512)
-            pl->kind = TK_L;
-        else if (avg >= 96 || tm > 32)
-            pl->kind = TK_M;
-        else
-            pl->kind = TK_S;
-        bm = pl->kind == TK_L ? CfgL::BM : pl->kind == TK_M ? CfgM::BM : CfgS::BM;
+        pl->kind = (avg >= 96 || tm > 32) ? TK_LM : TK_S;
+        bm = pl->kind == TK_LM ? CfgL::BM : CfgS::BM;
         pl->tl.BN1 = 128;
         pl->tl.BN2 = 256;
     }
+    pl->tl.BMS = pl->kind == TK_LM ? CfgM::BM : 0;
+    if (pl->tl.BMS % tm != 0) return MOE_ERR_UNSUPPORTED;
     if (bm % tm != 0) return MOE_ERR_UNSUPPORTED;
     pl->tl.BM = bm;
     pl->tl.NT1 = (p->f + pl->tl.BN1 - 1) / pl->tl.BN1;
     pl->tl.NT2 = (p->d + pl->tl.BN2 - 1) / pl->tl.BN2;
     pl->tl.maxRB = pl->N / bm + p->E;
-    pl->maxRB_layout = pl->N / 32 + p->E;  // layout does not depend on the tile choice
-    if ((long long)pl->tl.maxRB * (pl->tl.NT1 + pl->tl.NT2) > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
+    pl->maxRB_layout = pl->N / 32 + 2 * p->E;  // big plus small row blocks; the layout does not depend on the tile choice
+    if ((long long)(pl->tl.maxRB + p->E) * (pl->tl.NT1 + pl->tl.NT2) > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
     size_t o = 0;
     auto take = [&](size_t bytes) {
         size_t at = o;
@@ -355,6 +365,8 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     pl->o_dest_group_begin = take((size_t)(p->R + 1) * 4);
     pl->o_rb_base = take((size_t)(p->E + 1) * 4);
     pl->o_rb_expert = take((size_t)pl->maxRB_layout * 4);
+    pl->o_rbs_base = take((size_t)(p->E + 1) * 4);
+    pl->o_rbs_expert = take((size_t)p->E * 4);
     pl->o_h = take((size_t)pl->N * p->f * elem_size(p->dtype));
     // transposed gate weights (bf16 problems; unused when the routing is an input)
     pl->o_wgt = take(p->dtype == MOE_DT_BF16 ? (size_t)p->E * p->d * 2 : 0);
@@ -377,7 +389,7 @@ static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
     a->t_plan = pl.nRT;
     a->t_perm = a->t_plan + 1;
     a->t_g1 = a->t_perm + pl.nPB;
-    a->t_end = a->t_g1 + pl.tl.maxRB * (pl.tl.NT1 + pl.tl.NT2) + pl.nCT;
+    a->t_end = a->t_g1 + (pl.tl.maxRB + p.E) * (pl.tl.NT1 + pl.tl.NT2) + pl.nCT;
     char *ws = (char *)workspace;
     if (ws) {
         a->ctrl = (Ctrl *)(ws + pl.o_ctrl);
@@ -392,6 +404,8 @@ static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
         a->dest_group_begin = (int32_t *)(ws + pl.o_dest_group_begin);
         a->rb_base = (int32_t *)(ws + pl.o_rb_base);
         a->rb_expert = (int32_t *)(ws + pl.o_rb_expert);
+        a->rbs_base = (int32_t *)(ws + pl.o_rbs_base);
+        a->rbs_expert = (int32_t *)(ws + pl.o_rbs_expert);
         a->h = ws + pl.o_h;
         a->zero_bytes = pl.zero_bytes;
     }
@@ -414,16 +428,17 @@ static int set_smem(K kernel, size_t bytes) {
     return MOE_OK;
 }
 
-template <class P>
+template <class P, class PS>
 static int launch_mega(const Plan &pl, const KArgs &a_in, hipStream_t st) {
     size_t smem = tile_smem_bytes<P>();
+    if (tile_smem_bytes<PS>() > smem) smem = tile_smem_bytes<PS>();
     const size_t rsm = route_smem_bytes(pl.p.E, elem_size(pl.p.dtype));
     if (a_in.Wg && rsm > smem) smem = rsm;
     if (a_in.WgT && screen_smem_bytes(pl.p.E) > smem) smem = screen_smem_bytes(pl.p.E);
     if (plan_smem(pl) > smem) smem = plan_smem(pl);
     // decode tables live behind everything else, for the life of the workgroup
     KArgs a = a_in;
-    const size_t tab_bytes = (size_t)(2 * (pl.p.E + 1) + pl.tl.maxRB) * 4;
+    const size_t tab_bytes = (size_t)(3 * (pl.p.E + 1) + pl.tl.maxRB + pl.p.E) * 4;
     a.tab_lds_off = 0;
     if (tab_bytes <= 6 * 1024) {  // small enough that two workgroups of the 128-row tile still share a CU
         a.tab_lds_off = (int)align_up(smem, 16);
@@ -431,7 +446,7 @@ static int launch_mega(const Plan &pl, const KArgs &a_in, hipStream_t st) {
     }
     a.sched_lds_off = (int)align_up(smem, 16);
     smem = a.sched_lds_off + 16;
-    auto kern = k_megakernel<P>;
+    auto kern = k_megakernel<P, PS>;
     int rc = set_smem(kern, smem);
     if (rc) return rc;
     int dev = 0, cus = 0, per_cu = 0;
@@ -573,10 +588,9 @@ int moe_megakernel_forward(const moe_problem_t *p, const void *x, const void *Wg
     }
     hipStream_t st = (hipStream_t)stream;
     switch (pl.kind) {
-        case TK_F32: return launch_mega<F32Policy>(pl, a, st);
-        case TK_L: return launch_mega<Bf16Policy<CfgL>>(pl, a, st);
-        case TK_M: return launch_mega<Bf16Policy<CfgM>>(pl, a, st);
-        default: return launch_mega<Bf16Policy<CfgS>>(pl, a, st);
+        case TK_F32: return launch_mega<F32Policy, F32Policy>(pl, a, st);
+        case TK_LM: return launch_mega<Bf16Policy<CfgL>, Bf16Policy<CfgM>>(pl, a, st);
+        default: return launch_mega<Bf16Policy<CfgS>, Bf16Policy<CfgS>>(pl, a, st);
     }
 }
 
