@@ -33,7 +33,7 @@ struct Ctrl {
     u32 error;       // first device status (moe_status_t as positive number), 0 = ok
     u32 n_rb;        // (big) row blocks in use, all experts
     u32 n_flags;     // publish tiles / flags in use
-    u32 tile_next[8];  // per-XCD tile queues: next entry to hand out
+    u32 tile_next[4][8];  // tile queues, [GEMM1 big, GEMM1 small, GEMM2 big, GEMM2 small] x XCD: next entry to hand out
     u32 comb_next;     // next combine task
     u32 wgt_done;      // gate-weight transposition tasks finished
     u32 n_rbs;         // small row blocks in use (mixed tile heights), all experts
@@ -103,7 +103,7 @@ struct KArgs {
     void *WgT;                 // [E][d] transposed gate weights (bf16 problems with a gate), else NULL
     size_t zero_bytes;         // bytes from ctrl that must be zero between calls
     int tab_lds_off;           // megakernel: LDS offset of the cached decode tables, 0 = none
-    int sched_lds_off;         // megakernel: LDS offset of the tile loop's broadcast slots (16 bytes)
+    int sched_lds_off;         // megakernel: LDS offset of the task loops' broadcast slots (StageLds)
 };
 
 __device__ __forceinline__ u64 now_ticks() { return wall_clock64(); }

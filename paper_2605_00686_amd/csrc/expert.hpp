@@ -67,13 +67,13 @@ struct Tables {
 };
 
 // The row blocks [0, n) of one kind of all experts, in expert order, are cut
-// into kTileQueues contiguous shares, one per XCD.  The queue of an XCD lists
-// the GEMM1 tiles of its share of the big blocks, then of its share of the small
-// blocks, then the GEMM2 tiles in the same order; workgroups draw from the queue
-// of the XCD they run on (and from the others once it is empty).  Tiles that
-// read the same weights or the same rows therefore meet in one L2 instead of
-// fetching the operand once per XCD, and a GEMM2 tile only depends on entries
-// that come before it in its own queue.
+// into kTileQueues contiguous shares, one per XCD, and each share has four tile
+// lists: GEMM1 and GEMM2, for its big and for its small blocks.  Workgroups go
+// through the four kinds in the order GEMM1 big, GEMM1 small, GEMM2 big, GEMM2
+// small, and within a kind draw from the list of the XCD they run on first, then
+// from the others.  Tiles that read the same weights or the same rows therefore
+// meet in one L2 instead of fetching the operand once per XCD, and by the time
+// anybody draws a GEMM2 tile every GEMM1 tile has been drawn.
 struct TileQueue {
     int r0, r1;   // big row blocks of this share
     int s0, s1;   // small row blocks of this share
@@ -412,62 +412,85 @@ __device__ __forceinline__ void g2_tile(const KArgs &a, const TileInfo &ti, char
 // inlined into the kernel, so that the kernel's launch bounds govern it.
 struct StageLds {  // broadcast slots of a stage's task loop, in dynamic LDS at KArgs::sched_lds_off
     int next, ok;
+    int pick;  // tile stage: the list to draw from next, -1 = all lists are empty
 };
 
-// GEMM1 (GATED) or GEMM2 entries, big or SMALL row blocks, of tile queue q, starting with
-// entry `i` that the caller has drawn; returns the first entry drawn that is not its own.
+// One kind of tile (GEMM1 if GATED, else GEMM2; big or SMALL row blocks) from the eight tile
+// queues, the one of XCD `home` first, until none is left.
 template <class P, bool GATED, bool SMALL>
-__device__ __attribute__((noinline)) int tile_stage(KArgsAddr args, u32 smem_off, int q, int n_rb, int n_rbs, int i) {
+static __device__ __attribute__((noinline)) void tile_stage(KArgsAddr args, u32 smem_off, int home, int n_rb, int n_rbs) {
     KArgs a = load_kernel_args(args);
     mark_global(a);
     char *smem = lds_at((u32)uniform((int)smem_off));
-    q = uniform(q), n_rb = uniform(n_rb), n_rbs = uniform(n_rbs), i = uniform(i);
+    home = uniform(home), n_rb = uniform(n_rb), n_rbs = uniform(n_rbs);
     const int tid = threadIdx.x;
     Ctrl *c = a.ctrl;
     StageLds *sl = (StageLds *)(smem + a.sched_lds_off);
     const Tables tb = decode_tables(a, smem, n_rb, n_rbs);
-    const TileQueue tq = tile_queue(a, n_rb, n_rbs, q);
     const u64 t0 = kernel_start_ticks(c);
-    // queue layout: [GEMM1 big | GEMM1 small | GEMM2 big | GEMM2 small]
-    const int first = (GATED ? 0 : tq.n1()) + (SMALL ? (GATED ? tq.n1b : tq.n2b) : 0);
-    const int last = first + (GATED ? (SMALL ? tq.n1s : tq.n1b) : (SMALL ? tq.n2s : tq.n2b));
-    while (i >= first && i < last) {
-        // the next entry is drawn after this tile's main loop and consumed at the end of the tile
-        u32 next = 0x7fffffffu;
-        auto draw = [&]() {
-            if (tid == 0) next = atomicAdd(&c->tile_next[q], 1u);
-        };
-        MOE_TT_BEGIN();
-        if (GATED) {
-            const TileInfo ti = decode_tile<SMALL>(a, tb, tq, i - first, a.tl.NT1, P::BN1, a.f);
-            MOE_TT(c, 0);
-            g1_tile<P>(a, ti, smem, draw);
-            MOE_TT(c, 4);
-        } else {
-            const TileInfo ti = decode_tile<SMALL>(a, tb, tq, i - first, a.tl.NT2, P::BN2, a.d);
-            // h rows are written once, by GEMM1 tiles that released them before counting themselves
-            if (tid == 0) sl->ok = wait_ge<false>(c, &a.h_ready[ti.rb], (u32)a.tl.NT1) ? 1 : 0;
+    constexpr int LIST = (GATED ? 0 : 2) + (SMALL ? 1 : 0);
+    while (true) {
+        // one look at the eight counters of this kind picks the first list, from this XCD's on, that
+        // still has entries (a draw from an empty list costs a trip to memory and two barriers)
+        __syncthreads();
+        if (tid < 64) {
+            bool has = false;
+            if (tid < kTileQueues) {
+                const int qq = (home + tid) % kTileQueues;
+                const TileQueue t2 = tile_queue(a, n_rb, n_rbs, qq);
+                const int n2 = GATED ? (SMALL ? t2.n1s : t2.n1b) : (SMALL ? t2.n2s : t2.n2b);
+                has = ld_relaxed_agent(&c->tile_next[LIST][qq]) < (u32)n2;
+            }
+            const u64 m = __ballot(has);
+            if (tid == 0) sl->pick = m ? (home + __ffsll((long long)m) - 1) % kTileQueues : -1;
+        }
+        __syncthreads();
+        const int q = uniform(sl->pick);
+        if (q < 0) break;
+        const TileQueue tq = tile_queue(a, n_rb, n_rbs, q);
+        const int n = GATED ? (SMALL ? tq.n1s : tq.n1b) : (SMALL ? tq.n2s : tq.n2b);
+        u32 *counter = &c->tile_next[LIST][q];
+        __syncthreads();
+        if (tid == 0) sl->next = (int)atomicAdd(counter, 1u);
+        __syncthreads();
+        int i = uniform(sl->next);
+        while (i < n) {
+            // the next entry is drawn after this tile's main loop and consumed at the end of the tile
+            u32 next = 0x7fffffffu;
+            auto draw = [&]() {
+                if (tid == 0) next = atomicAdd(counter, 1u);
+            };
+            MOE_TT_BEGIN();
+            if (GATED) {
+                const TileInfo ti = decode_tile<SMALL>(a, tb, tq, i, a.tl.NT1, P::BN1, a.f);
+                MOE_TT(c, 0);
+                g1_tile<P>(a, ti, smem, draw);
+                MOE_TT(c, 4);
+            } else {
+                const TileInfo ti = decode_tile<SMALL>(a, tb, tq, i, a.tl.NT2, P::BN2, a.d);
+                // h rows are written once, by GEMM1 tiles that released them before counting themselves
+                if (tid == 0) sl->ok = wait_ge<false>(c, &a.h_ready[ti.rb], (u32)a.tl.NT1) ? 1 : 0;
+                __syncthreads();
+                MOE_TT(c, 5);
+                if (sl->ok)
+                    g2_tile<P>(a, ti, smem, draw);
+                else
+                    draw();
+                MOE_TT(c, 9);
+            }
             __syncthreads();
-            MOE_TT(c, 5);
-            if (sl->ok)
-                g2_tile<P>(a, ti, smem, draw);
-            else
-                draw();
-            MOE_TT(c, 9);
-        }
-        __syncthreads();
-        if (tid == 0) {
-            mark_phase_end(c, GATED ? 3 : 4, t0);
-            sl->next = (int)next;
-        }
-        __syncthreads();
-        i = uniform(sl->next);
-        MOE_TT(c, 10);
+            if (tid == 0) {
+                mark_phase_end(c, GATED ? 3 : 4, t0);
+                sl->next = (int)next;
+            }
+            __syncthreads();
+            i = uniform(sl->next);
+            MOE_TT(c, 10);
 #ifdef MOE_TILE_TIMING
-        if (tid == 0) atomicMax(&c->dbg[(GATED ? 16 : 24) + q], now_ticks() - c->t0);
+            if (tid == 0) atomicMax(&c->dbg[24 + q], now_ticks() - c->t0);
 #endif
+        }
     }
-    return i;
 }
 
 // ---- combine

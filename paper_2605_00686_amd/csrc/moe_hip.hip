@@ -137,14 +137,13 @@ __device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
 // The whole layer in one persistent kernel.  Every workgroup walks through three
 // stages, drawing work from counters in the control block:
 //   1. front tasks, one counter, in this order: [gate tasks | plan | permutation blocks];
-//   2. GEMM tiles, one queue per XCD (see TileQueue): its own XCD's queue first, then the
-//      others, each queue listing its GEMM1 tiles before its GEMM2 tiles;
+//   2. GEMM tiles, four kinds in turn (GEMM1 then GEMM2, big then small row blocks), each kind
+//      from one list per XCD (see TileQueue): its own XCD's list first, then the others;
 //   3. combine tasks, one counter.
 // No wait can deadlock, whatever the grid size: a task only waits for tasks of an
-// earlier kind (permutation <- plan <- gate, GEMM1 <- permutation, GEMM2 <- GEMM1 tiles
-// earlier in the same queue, combine <- GEMM2), a workgroup only moves to a later stage
-// or to another queue when every entry before has been drawn, and whoever drew an entry
-// is running it.  So the not yet finished entry of the earliest kind is always either
+// earlier kind (permutation <- plan <- gate, GEMM1 <- permutation, GEMM2 <- GEMM1,
+// combine <- GEMM2), a workgroup only moves on to a later kind when every entry of the
+// kinds before has been drawn, and whoever drew an entry is running it.  So the not yet finished entry of the earliest kind is always either
 // running with everything it needs, or about to be drawn by a workgroup that is not
 // waiting.  A workgroup draws its next entry while it works on the current one, which
 // hides the counter's latency.  The kernel body itself only strings the stage
@@ -200,23 +199,18 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
     bad = bad || !s_ok;
 
     if (!bad) {
-        // ---- stage 2: GEMM tiles, this XCD's queue first
+        // ---- stage 2: GEMM tiles, one call per kind, this XCD's lists first
         const int home = xcd_id() % kTileQueues;
-        for (int s = 0; s < kTileQueues; ++s) {
-            const int q = (home + s) % kTileQueues;
-            const TileQueue tq = tile_queue(a, n_rb, n_rbs, q);
-            const int n_entries = tq.total();
-            if (n_entries == 0) continue;
-            __syncthreads();
-            if (tid == 0) s_task = (int)atomicAdd(&c->tile_next[q], 1u);
-            __syncthreads();
-            int i = s_task;
-            const u32 lds = lds_offset(smem);
-            if (i < tq.n1b) i = tile_stage<P, true, false>(kargs, lds, q, n_rb, n_rbs, i);
-            if (MIXED && i >= tq.n1b && i < tq.n1()) i = tile_stage<PS, true, true>(kargs, lds, q, n_rb, n_rbs, i);
-            if (i >= tq.n1() && i < tq.n1() + tq.n2b) i = tile_stage<P, false, false>(kargs, lds, q, n_rb, n_rbs, i);
-            if (MIXED && i >= tq.n1() + tq.n2b && i < n_entries) i = tile_stage<PS, false, true>(kargs, lds, q, n_rb, n_rbs, i);
-        }
+        const u32 lds = lds_offset(smem);
+        MOE_TT_BEGIN();
+        tile_stage<P, true, false>(kargs, lds, home, n_rb, n_rbs);
+        MOE_TT(c, 20);
+        if (MIXED && n_rbs > 0) tile_stage<PS, true, true>(kargs, lds, home, n_rb, n_rbs);
+        MOE_TT(c, 21);
+        tile_stage<P, false, false>(kargs, lds, home, n_rb, n_rbs);
+        MOE_TT(c, 22);
+        if (MIXED && n_rbs > 0) tile_stage<PS, false, true>(kargs, lds, home, n_rb, n_rbs);
+        MOE_TT(c, 23);
 #ifdef MOE_TILE_TIMING
         if (tid == 0) {
             const u64 t = now_ticks() - c->t0;
@@ -262,6 +256,8 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
             printf("plan starts at %.2f us; ", c->dbg[39] / 100.);
             printf("plan (us): stage %.2f, expert scans %.2f, block scan %.2f, flags %.2f, write-back %.2f\n", c->dbg[34] / 100.,
                    c->dbg[35] / 100., c->dbg[36] / 100., c->dbg[37] / 100., c->dbg[38] / 100.);
+            printf("stage calls (us per workgroup): g1 big %.1f, g1 small %.1f, g2 big %.1f, g2 small %.1f\n", c->dbg[20] / (double)gridDim.x / 100.,
+                   c->dbg[21] / (double)gridDim.x / 100., c->dbg[22] / (double)gridDim.x / 100., c->dbg[23] / (double)gridDim.x / 100.);
             printf("tiles done (us): avg over workgroups %.1f, last %.1f; per queue g1 end", c->dbg[14] / (double)gridDim.x / 100., c->dbg[15] / 100.);
             for (int q = 0; q < 8; ++q) printf(" %.0f", c->dbg[16 + q] / 100.);
             printf("; g2 end");
@@ -445,7 +441,7 @@ static int launch_mega(const Plan &pl, const KArgs &a_in, hipStream_t st) {
         smem = a.tab_lds_off + tab_bytes;
     }
     a.sched_lds_off = (int)align_up(smem, 16);
-    smem = a.sched_lds_off + 16;
+    smem = a.sched_lds_off + sizeof(StageLds);
     auto kern = k_megakernel<P, PS>;
     int rc = set_smem(kern, smem);
     if (rc) return rc;
