@@ -418,7 +418,8 @@ struct StageLds {  // broadcast slots of a stage's task loop, in dynamic LDS at 
 // One kind of tile (GEMM1 if GATED, else GEMM2; big or SMALL row blocks) from the eight tile
 // queues, the one of XCD `home` first, until none is left.
 template <class P, bool GATED, bool SMALL>
-static __device__ __attribute__((noinline)) void tile_stage(KArgsAddr args, u32 smem_off, int home, int n_rb, int n_rbs) {
+static __device__ __attribute__((noinline)) void tile_stage(KArgsAddr args, u32 smem_off, int home, int n_rb, int n_rbs,
+                                                           volatile int *caller_local) {
     KArgs a = load_kernel_args(args);
     mark_global(a);
     char *smem = lds_at((u32)uniform((int)smem_off));
@@ -429,6 +430,7 @@ static __device__ __attribute__((noinline)) void tile_stage(KArgsAddr args, u32 
     const Tables tb = decode_tables(a, smem, n_rb, n_rbs);
     const u64 t0 = kernel_start_ticks(c);
     constexpr int LIST = (GATED ? 0 : 2) + (SMALL ? 1 : 0);
+    *caller_local = LIST;  // (see the call sites)
     while (true) {
         // one look at the eight counters of this kind picks the first list, from this XCD's on, that
         // still has entries (a draw from an empty list costs a trip to memory and two barriers)

@@ -202,14 +202,19 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
         // ---- stage 2: GEMM tiles, one call per kind, this XCD's lists first
         const int home = xcd_id() % kTileQueues;
         const u32 lds = lds_offset(smem);
+        // The stage functions get the address of a local of this kernel.  That keeps the compiler from
+        // marking the calls as tail calls, which is what lets it drop the saving and restoring of
+        // callee-saved registers in these functions (they have one caller, which keeps nothing in them):
+        // some 270 registers per lane through scratch memory, per call, otherwise.
+        volatile int stage_mark = 0;
         MOE_TT_BEGIN();
-        tile_stage<P, true, false>(kargs, lds, home, n_rb, n_rbs);
+        tile_stage<P, true, false>(kargs, lds, home, n_rb, n_rbs, &stage_mark);
         MOE_TT(c, 20);
-        if (MIXED && n_rbs > 0) tile_stage<PS, true, true>(kargs, lds, home, n_rb, n_rbs);
+        if (MIXED && n_rbs > 0) tile_stage<PS, true, true>(kargs, lds, home, n_rb, n_rbs, &stage_mark);
         MOE_TT(c, 21);
-        tile_stage<P, false, false>(kargs, lds, home, n_rb, n_rbs);
+        tile_stage<P, false, false>(kargs, lds, home, n_rb, n_rbs, &stage_mark);
         MOE_TT(c, 22);
-        if (MIXED && n_rbs > 0) tile_stage<PS, false, true>(kargs, lds, home, n_rb, n_rbs);
+        if (MIXED && n_rbs > 0) tile_stage<PS, false, true>(kargs, lds, home, n_rb, n_rbs, &stage_mark);
         MOE_TT(c, 23);
 #ifdef MOE_TILE_TIMING
         if (tid == 0) {
