@@ -66,11 +66,15 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
         segb = segc + E * R;
         nfl = segb + E * R;  // [R][E]
         s_free = nfl + E * R;
-        if (!a.seg_from_blocks)
+        if (!a.seg_from_blocks) {
+#pragma unroll 8
             for (int q = tid; q < E * R; q += kThreads) segc[q] = a.seg_cnt[q];
+        }
     }
     if (hist_lds) hist = s_free;
-    for (int q = tid; q < nPB * E; q += kThreads) hist[q] = a.blk_hist[q];  // (blk_base <- blk_hist if not in LDS)
+    // (independent loads, several in flight per thread; blk_base <- blk_hist if not in LDS)
+#pragma unroll 8
+    for (int q = tid; q < nPB * E; q += kThreads) hist[q] = a.blk_hist[q];
     __syncthreads();
     if (a.seg_from_blocks) {  // a destination is a whole number of blocks: add up its blocks' histograms
         const int bpd = a.per_dest / kPermBlock;
