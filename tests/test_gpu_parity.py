@@ -128,6 +128,25 @@ def test_megakernel_gate_many_experts_and_ties():
     np.testing.assert_allclose(buf.topk_w.cpu().numpy()[40:44], 0.25, rtol=1e-6)
 
 
+@pytest.mark.parametrize("cfg", [
+    # k = E, destinations that are not whole token blocks, 64 x 128 publish tile
+    dict(T=200, d=128, E=5, k=5, f=192, R=4, dtype="bf16", seed=31, tile_m=64, tile_n=128),
+    # odd everything, one expert per token, fp32
+    dict(T=130, d=64, E=3, k=1, f=64, R=2, dtype="f32", seed=32),
+    # one destination, 32-row publish tile with many rows per expert (256-row compute tiles)
+    dict(T=512, d=256, E=2, k=2, f=128, R=1, dtype="bf16", seed=33, tile_m=32),
+    # more destinations than a wavefront has lanes, tiny segments
+    dict(T=256, d=128, E=16, k=2, f=64, R=128, dtype="bf16", seed=34, tile_m=32),
+], ids=["k_eq_E", "odd_f32", "one_dest", "many_dest"])
+@pytest.mark.parametrize("signal_mode", [0, 1])
+def test_megakernel_odd_shapes(cfg, signal_mode):
+    B = _binding()
+    print(f"case {cfg} signal_mode {signal_mode}", flush=True)
+    inp = W.make_inputs(cfg)
+    p, buf = run_forward(B, inp, signal_mode, 0)
+    check_against_oracle(B, inp, p, buf, signal_mode)
+
+
 def test_megakernel_system_scope_and_reuse():
     """Same buffers, three calls in a row with rising epochs, both scopes and
     both modes: the workspace must come back clean each time."""
