@@ -390,48 +390,57 @@ __device__ __forceinline__ bool route_screened(const KArgs &a, int t0, char *sme
     __syncthreads();
     MOE_TT(a.ctrl, 40);
 
-    // ---- threshold and candidates, one token per wavefront at a time
+    // ---- threshold and candidates: the wavefront's four tokens side by side (independent chains)
+    {
+        u32 klo[TPW][4], khi[TPW][4], K[TPW];
 #pragma unroll
-    for (int i = 0; i < TPW; ++i) {
-        const int tl = wave + 4 * i;
-        u32 klo[4], khi[4];
+        for (int i = 0; i < TPW; ++i) {
+            const int tl = wave + 4 * i;
+            K[i] = 0u;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int e = lane + 64 * q;
-            if (e < E) {
-                const float l = Ls[tl * E + e], eps = As[tl * E + e];
-                klo[q] = float_key(l - eps);
-                khi[q] = float_key(l + eps);
-            } else {
-                klo[q] = 0u;
-                khi[q] = 0u;
+            for (int q = 0; q < 4; ++q) {
+                const int e = lane + 64 * q;
+                klo[i][q] = 0u;
+                khi[i][q] = 0u;
+                if (e < E) {
+                    const float l = Ls[tl * E + e], eps = As[tl * E + e];
+                    klo[i][q] = float_key(l - eps);
+                    khi[i][q] = float_key(l + eps);
+                }
             }
         }
-        // the k-th largest lower bound: largest key K with at least k lower bounds >= K
-        u32 K = 0u;
-        for (int bit = 31; bit >= 0; --bit) {
-            const u32 trial = K | (1u << bit);
-            int cnt = 0;
+        // the k-th largest lower bound: largest key K with at least k lower bounds >= K, found bit by
+        // bit; the lowest 8 bits are left zero (a slightly smaller threshold is still a valid one)
+        for (int bit = 31; bit >= 8; --bit) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (64 * q < E) cnt += __popcll(__ballot(klo[q] >= trial));
-            if (cnt >= k) K = trial;
-        }
-        int before = 0, mine[4], n = 0;
+            for (int i = 0; i < TPW; ++i) {
+                const u32 trial = K[i] | (1u << bit);
+                int cnt = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const bool in = (lane + 64 * q < E) && khi[q] >= K;
-            const u64 m = __ballot(in);
-            mine[q] = in ? before + __popcll(m & ((1ull << lane) - 1ull)) : -1;
-            before += __popcll(m);
+                for (int q = 0; q < 4; ++q)
+                    if (64 * q < E) cnt += __popcll(__ballot(klo[i][q] >= trial));
+                if (cnt >= k) K[i] = trial;
+            }
         }
-        n = before;
-        if (n <= kMaxCand) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (mine[q] >= 0) cand[tl * kMaxCand + mine[q]] = lane + 64 * q;
+        for (int i = 0; i < TPW; ++i) {
+            const int tl = wave + 4 * i;
+            int before = 0, mine[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const bool in = (lane + 64 * q < E) && khi[i][q] >= K[i];
+                const u64 m = __ballot(in);
+                mine[q] = in ? before + __popcll(m & ((1ull << lane) - 1ull)) : -1;
+                before += __popcll(m);
+            }
+            const int n = before;
+            if (n <= kMaxCand) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (mine[q] >= 0) cand[tl * kMaxCand + mine[q]] = lane + 64 * q;
+            }
+            if (lane == 0) s_ncand[tl] = (n <= kMaxCand) ? n : 0;
         }
-        if (lane == 0) s_ncand[tl] = (n <= kMaxCand) ? n : 0;
     }
     __syncthreads();
     bool ok = true;  // (tokens past T repeat token T-1: they fail only if it does)
