@@ -83,9 +83,10 @@ typedef struct {
 
 /* number of 64-bit counters moe_megakernel_forward writes to `stats` */
 #define MOE_NUM_STATS 16
-/* stats[0] release fences issued right before flag stores (per tile, or per destination)
+/* stats[0] release fences issued right before flag stores (per tile, or per fence group:
+ *          a destination, or group_size of its flags)
  * stats[1] flags stored                 stats[2] publish tiles written
- * stats[3] per-compute-tile releases that only feed a destination counter (PER_DEST)
+ * stats[3] per-compute-tile releases that only feed a fence-group counter (PER_DEST)
  * stats[4] GEMM1 compute tiles          stats[5] GEMM2 compute tiles
  * stats[6] bounded waits that expired   stats[7] device status (a moe_status_t, 0 = ok)
  * stats[8..13] in-kernel timeline: nanoseconds from the first task drawn to the end of
