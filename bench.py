@@ -6,7 +6,8 @@ publish with flags, combine) in one persistent-kernel launch over one batch of
 seeded synthetic input already resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
-                  [--signal-mode per_dest|per_tile] [--scope agent|system] [--group-size G] [--ops] [--no-cpu]
+                  [--signal-mode per_dest|per_tile] [--scope agent|system] [--group-size G] [--scheduler static|ready_queue]
+                  [--ops] [--no-cpu]
 """
 from __future__ import annotations
 
@@ -112,6 +113,8 @@ def main():
     ap.add_argument("--scope", default="agent", choices=["agent", "system"])
     ap.add_argument("--group-size", type=int, default=0,
                     help="per_dest only: flags per fence group (0 = all flags of a destination)")
+    ap.add_argument("--scheduler", default="static", choices=["static", "ready_queue"],
+                    help="order of expert tiles and combine tasks: dependency-ordered lists, or ready queues")
     ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens for the CPU baseline (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -135,7 +138,8 @@ def main():
     mode = B.MOE_SIGNAL_PER_DEST if args.signal_mode == "per_dest" else B.MOE_SIGNAL_PER_TILE
     scope = B.MOE_SCOPE_AGENT if args.scope == "agent" else B.MOE_SCOPE_SYSTEM
     p = B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
-                  tile_n=cfg["tile_n"], signal_mode=mode, fence_scope=scope, epoch=1, group_size=args.group_size)
+                  tile_n=cfg["tile_n"], signal_mode=mode, fence_scope=scope, epoch=1, group_size=args.group_size,
+                  scheduler=1 if args.scheduler == "ready_queue" else 0)
     buf = B.Buffers(p)
     dev = {n: (inp[n].cuda() if inp[n] is not None else None) for n in ("x", "Wg", "gate_bias", "W1", "W3", "W2")}
     if cfg["prerouted"] is not None:
@@ -183,6 +187,7 @@ def main():
         "config": {"workload": f"{args.workload}: T={cfg['T']} d={cfg['d']} E={cfg['E']} k={cfg['k']} f={cfg['f']} "
                                f"R={cfg['R']} tile={cfg['tile_m']}x{cfg['tile_n']}",
                    "signal_mode": args.signal_mode, "fence_scope": args.scope, "group_size": args.group_size,
+                   "scheduler": args.scheduler,
                    "launches_per_step": 1},
         "roofline": {"bound": "hbm", "kernel": "k_megakernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
@@ -192,6 +197,7 @@ def main():
                  "frac": flops / (avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF, "flops": flops},
         "signaling": {"fences": stats[0], "flags": stats[1], "publish_tiles": stats[2], "writer_releases": stats[3],
                       "gemm1_tiles": stats[4], "gemm2_tiles": stats[5]},
+        "scheduling": {"ready_queue_tasks": stats[16], "gemm2_tiles_run_ahead_of_waiting_gemm1_tiles": stats[17]},
         "timeline_us": {"gate_end": stats[8] / 1e3, "plan_end": stats[9] / 1e3, "perm_end": stats[10] / 1e3,
                         "gemm1_end": stats[11] / 1e3, "gemm2_end": stats[12] / 1e3, "combine_end": stats[13] / 1e3,
                         "wait_sum": stats[14] / 1e3, "workgroups": stats[15]},

@@ -62,6 +62,20 @@ typedef enum { MOE_SIGNAL_PER_TILE = 0, MOE_SIGNAL_PER_DEST = 1 } moe_signal_mod
  * accesses themselves: this GPU only, or GPU + host + peers. */
 typedef enum { MOE_SCOPE_AGENT = 0, MOE_SCOPE_SYSTEM = 1 } moe_fence_scope_t;
 
+/* How the persistent kernel orders the expert tiles and the combine tasks (section 2.3:
+ * tasks run as soon as their inputs are there):
+ *   STATIC       dependency-ordered lists: every GEMM1 tile is handed out before any
+ *                GEMM2 tile, every GEMM2 tile before any combine task; a task that finds
+ *                its input unfinished waits for it.
+ *   READY_QUEUE  tasks are enqueued by the event that makes them runnable and taken in
+ *                that order: the workgroup that finishes the last GEMM1 tile of a row
+ *                block enqueues the block's GEMM2 tiles; the workgroup that stores the
+ *                last flag of a destination enqueues the combine tasks of the
+ *                destination's tokens.  Workgroups take ready tasks before new GEMM1
+ *                tiles, so GEMM2 tiles and combine tasks start out of order and nothing
+ *                that was taken ever waits.  Results are identical. */
+typedef enum { MOE_SCHED_STATIC = 0, MOE_SCHED_READY_QUEUE = 1 } moe_scheduler_t;
+
 typedef struct {
     int32_t T, d, E, k, f, R; /* R must divide T                                   */
     int32_t dtype;            /* moe_dtype_t                                        */
@@ -79,10 +93,11 @@ typedef struct {
                               /* consecutive flags of a destination, one fence per  */
                               /* group: fences = sum over r of ceil(n_r / g).  Must */
                               /* be 0 for MOE_SIGNAL_PER_TILE                       */
+    int32_t scheduler;        /* moe_scheduler_t (moe_megakernel_forward only)      */
 } moe_problem_t;
 
 /* number of 64-bit counters moe_megakernel_forward writes to `stats` */
-#define MOE_NUM_STATS 16
+#define MOE_NUM_STATS 20
 /* stats[0] release fences issued right before flag stores (per tile, or per fence group:
  *          a destination, or group_size of its flags)
  * stats[1] flags stored                 stats[2] publish tiles written
@@ -93,7 +108,11 @@ typedef struct {
  *   the last gate task [8], the plan [9], the last permutation block [10], the last
  *   GEMM1 tile [11], the last GEMM2 tile [12], the last combine task [13]
  * stats[14] nanoseconds workgroups spent waiting on dependencies, summed over workgroups
- * stats[15] workgroups launched */
+ * stats[15] workgroups launched
+ * stats[16..17] MOE_SCHED_READY_QUEUE only (else 0): tasks taken from the ready queues [16];
+ *   GEMM2 tiles among them that a workgroup ran while GEMM1 tiles were still waiting to be
+ *   handed out [17]
+ * stats[18..19] reserved (0) */
 
 /* Host, pure: bytes of workspace a problem needs / upper bound on the number
  * of flags (uint32 each) the caller must provide; 0 if the problem is invalid. */
@@ -105,7 +124,9 @@ const char *moe_status_string(int status);
 
 /* Zero the control part of a fresh workspace.  Call once after allocating it
  * (and again after a call reported MOE_ERR_TIMEOUT); every other entry point
- * leaves the workspace ready for the next call. */
+ * leaves the workspace ready for the next call.  Size and layout of the workspace
+ * depend on T, d, E, k, f, R, dtype, tile_m and tile_n only: signal_mode,
+ * fence_scope, epoch, group_size and scheduler may change from call to call. */
 int moe_workspace_init(const moe_problem_t *p, void *workspace, void *stream);
 
 /*

@@ -18,7 +18,8 @@ MOE_ERR_NOT_READY, MOE_ERR_HIP, MOE_ERR_TIMEOUT, MOE_ERR_BAD_ROUTING = -4, -5, -
 MOE_DT_F32, MOE_DT_BF16 = 0, 1
 MOE_SIGNAL_PER_TILE, MOE_SIGNAL_PER_DEST = 0, 1
 MOE_SCOPE_AGENT, MOE_SCOPE_SYSTEM = 0, 1
-MOE_NUM_STATS = 16
+MOE_SCHED_STATIC, MOE_SCHED_READY_QUEUE = 0, 1
+MOE_NUM_STATS = 20
 
 EXPORTS = ("moe_workspace_bytes", "moe_num_flags", "moe_status_string", "moe_workspace_init", "moe_route",
            "moe_dispatch", "moe_megakernel_forward", "moe_combine")
@@ -27,7 +28,8 @@ EXPORTS = ("moe_workspace_bytes", "moe_num_flags", "moe_status_string", "moe_wor
 class MoeProblem(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("T", "d", "E", "k", "f", "R", "dtype", "tile_m", "tile_n",
                                               "signal_mode", "fence_scope")] + [("epoch", ctypes.c_uint32),
-                                                                                 ("group_size", ctypes.c_int32)]
+                                                                                 ("group_size", ctypes.c_int32),
+                                                                                 ("scheduler", ctypes.c_int32)]
 
 
 class MoeError(RuntimeError):
@@ -56,12 +58,12 @@ for _n in ("moe_workspace_init", "moe_route", "moe_dispatch", "moe_megakernel_fo
 
 
 def problem(T, d, E, k, f, R, dtype, tile_m=0, tile_n=0, signal_mode=MOE_SIGNAL_PER_DEST,
-            fence_scope=MOE_SCOPE_AGENT, epoch=1, group_size=0) -> MoeProblem:
+            fence_scope=MOE_SCOPE_AGENT, epoch=1, group_size=0, scheduler=0) -> MoeProblem:
     if isinstance(dtype, torch.dtype):
         dtype = MOE_DT_F32 if dtype == torch.float32 else MOE_DT_BF16
     elif isinstance(dtype, str):
         dtype = MOE_DT_F32 if dtype == "f32" else MOE_DT_BF16
-    return MoeProblem(T, d, E, k, f, R, dtype, tile_m, tile_n, signal_mode, fence_scope, epoch, group_size)
+    return MoeProblem(T, d, E, k, f, R, dtype, tile_m, tile_n, signal_mode, fence_scope, epoch, group_size, scheduler)
 
 
 def _ptr(t):

@@ -38,6 +38,8 @@ struct Ctrl {
     u32 wgt_done;      // gate-weight transposition tasks finished
     u32 n_rbs;         // small row blocks in use (mixed tile heights), all experts
     u32 pad[5];
+    u32 rq_head[8];    // ready queues, one per XCD: next entry to take ...
+    u32 rq_tail[8];    // ... and next free entry
     u64 t0;          // wall-clock tick of the first task drawn
     u64 stats[MOE_NUM_STATS];
 #ifdef MOE_TILE_TIMING
@@ -61,6 +63,7 @@ struct KArgs {
     int T, d, E, k, f, R;
     int dtype, tile_m, tile_n, signal_mode, fence_scope;
     int group_size;  // flags per fence group of the per-destination mode, 0 = all flags of a destination
+    int scheduler;   // moe_scheduler_t
     u32 epoch;
     int N, per_dest, ncb;  // slots, tokens per destination, column blocks per row
     int nPB, nRT, nCT;     // permutation blocks, gate tasks, combine tasks
@@ -101,6 +104,9 @@ struct KArgs {
     u32 *h_ready;              // [maxRB] GEMM1 tiles finished per row block
     void *h;                   // [N][f]
     void *WgT;                 // [E][d] transposed gate weights (bf16 problems with a gate), else NULL
+    u32 *dest_done;            // [R] flags stored so far per destination (ready-queue scheduler), else NULL
+    u32 *rq_slots;             // [8][rq_cap] ready-queue entries, 0 = empty (ready-queue scheduler), else NULL
+    int rq_cap;                // entries per ready queue: all GEMM2 tiles plus all combine tasks
     size_t zero_bytes;         // bytes from ctrl that must be zero between calls
     int tab_lds_off;           // megakernel: LDS offset of the cached decode tables, 0 = none
     int sched_lds_off;         // megakernel: LDS offset of the task loops' broadcast slots (StageLds)

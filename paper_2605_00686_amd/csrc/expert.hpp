@@ -125,6 +125,71 @@ __device__ __forceinline__ TileInfo decode_tile(const KArgs &a, const Tables &tb
     return ti;
 }
 
+// The tile (row block rb of its kind, column tile ct): how the ready-queue scheduler names a
+// GEMM2 tile.
+template <bool SMALL>
+__device__ __forceinline__ TileInfo decode_block_tile(const KArgs &a, const Tables &tb, int rb, int ct, int BN,
+                                                      int total_cols) {
+    TileInfo ti;
+    const int BMK = SMALL ? a.tl.BMS : a.tl.BM;
+    const int e = (SMALL ? tb.rbs_expert : tb.rb_expert)[rb];
+    ti.e = e;
+    ti.rb = SMALL ? tb.n_rb + rb : rb;
+    ti.lrow0 = SMALL ? (tb.rb_base[e + 1] - tb.rb_base[e]) * a.tl.BM : (rb - tb.rb_base[e]) * BMK;
+    ti.row0 = tb.offsets[e] + ti.lrow0;
+    ti.nrows = min(BMK, tb.offsets[e + 1] - ti.row0);
+    ti.n0 = ct * BN;
+    ti.ncols = min(BN, total_cols - ti.n0);
+    ti.valid = true;
+    return ti;
+}
+
+// ---- ready queues (MOE_SCHED_READY_QUEUE).  One queue per XCD.  Every task that goes through
+// a queue has a fixed one: the GEMM2 tiles of a row block go to the queue of the XCD whose share
+// (see TileQueue) the block is in, the combine tasks of destination r to queue r mod 8; so the
+// number of entries each queue will receive is known once the plan is.  A queue is an array of
+// entries that starts all zero, a tail counter with which producers reserve entries, and a head
+// counter from which consumers draw tickets: ticket t is the right, and the duty, to run entry t
+// of that queue, whenever it gets written.  A consumer empties the entry it ran, so the array is
+// all zero again after the call.  An entry is 1 + (row block * NT2 + column tile) for a GEMM2 tile
+// (row blocks numbered as in h_ready) or kReadyCombine | task for a combine task.
+constexpr u32 kReadyCombine = 0x80000000u;
+// entries queue q receives in this call
+__device__ __forceinline__ int ready_queue_size(const KArgs &a, int n_rb, int n_rbs, int q) {
+    const TileQueue tq = tile_queue(a, n_rb, n_rbs, q);
+    const int dests = a.R > q ? (a.R - q + kTileQueues - 1) / kTileQueues : 0;
+    return tq.n2b + tq.n2s + dests * (a.per_dest / a.comb_tokens);
+}
+// the share that row block rb of n (of one kind) lies in
+__device__ __forceinline__ int ready_queue_of_block(int n, int rb) {
+    int q = 0;
+    while (q + 1 < kTileQueues && rb >= (int)(((long long)n * (q + 1)) / kTileQueues)) ++q;
+    return q;
+}
+// `n` consecutive entries first, first + 1, ... to queue q, by all lanes of one wavefront
+__device__ __forceinline__ void ready_push(const KArgs &a, int q, u32 first, int n, int lane) {
+    u32 base = 0;
+    if (lane == 0) base = atomicAdd(&a.ctrl->rq_tail[q], (u32)n);
+    base = (u32)__builtin_amdgcn_readfirstlane((int)base);
+    u32 *slots = a.rq_slots + (size_t)q * a.rq_cap;
+    for (int i = lane; i < n; i += 64)
+        if (base + i < (u32)a.rq_cap) st_relaxed(&slots[base + i], first + (u32)i, 0);
+}
+// Wavefront-wide: `n` more flags of destination dst carry the epoch.  Whoever reports the
+// last ones enqueues the combine tasks of the destination's tokens (the host makes combine
+// tasks lie inside one destination for this scheduler).  The consumer still checks the
+// flags itself before it reads a row, so no ordering beyond the counter is needed here.
+__device__ __forceinline__ void ready_flags_stored(const KArgs &a, int dst, int n, int lane) {
+    u32 old = 0;
+    if (lane == 0) old = atomicAdd(&a.dest_done[dst], (u32)n);
+    old = (u32)__builtin_amdgcn_readfirstlane((int)old);
+    const u32 all = (u32)(a.dest_flag_begin[dst + 1] - a.dest_flag_begin[dst]);
+    if (old + (u32)n == all) {
+        const int per = a.per_dest / a.comb_tokens;
+        ready_push(a, dst % kTileQueues, kReadyCombine | (u32)(dst * per), per, lane);
+    }
+}
+
 // Every pointer of the argument block, marked as pointing to global memory
 // (see as_global).
 __device__ __forceinline__ void mark_global(KArgs &a) {
@@ -159,6 +224,8 @@ __device__ __forceinline__ void mark_global(KArgs &a) {
     a.rbs_expert = as_global(a.rbs_expert);
     a.h_ready = as_global(a.h_ready);
     a.h = as_global((char *)a.h);
+    a.dest_done = as_global(a.dest_done);
+    a.rq_slots = as_global(a.rq_slots);
 }
 
 // The decode tables: the copies a workgroup made in LDS after the plan (see the
@@ -188,8 +255,9 @@ __device__ __forceinline__ Tables decode_tables(const KArgs &a, char *smem, int 
 // never materialised.
 // `after_gemm()` runs between the main loop and the write-out (the megakernel draws
 // its next tile there, so that the counter's latency hides behind the write-out).
+// Returns, in thread 0, how many GEMM1 tiles of the row block had finished before this one.
 template <class P, class Hook>
-__device__ __forceinline__ void g1_tile(const KArgs &a, const TileInfo &ti, char *smem, Hook after_gemm) {
+__device__ __forceinline__ u32 g1_tile(const KArgs &a, const TileInfo &ti, char *smem, Hook after_gemm) {
     using ET = typename P::ET;
     const ET *x = (const ET *)a.x;
     const int N = a.N;
@@ -212,12 +280,14 @@ __device__ __forceinline__ void g1_tile(const KArgs &a, const TileInfo &ti, char
     }
     sync_stores();
     MOE_TT(a.ctrl, 2);
+    u32 before = 0;
     if (threadIdx.x == 0) {
         fence_release(0);
-        atomicAdd(&a.h_ready[ti.rb], 1u);
+        before = atomicAdd(&a.h_ready[ti.rb], 1u);
         atomicAdd(&a.ctrl->stats[4], 1ull);
     }
     MOE_TT(a.ctrl, 3);
+    return before;
 }
 
 // Publish the y tile sitting in the LDS C tile.  A publish tile is the part of
@@ -314,6 +384,9 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
             atomicAdd(&a.ctrl->stats[1], n);
             atomicAdd(&a.ctrl->stats[2], n);
         }
+        // (the flags were stored by lane 0 of this wavefront)
+        if (a.dest_done && wave == 0)
+            for (int i = 0; i < nseg; ++i) ready_flags_stored(a, s_dest[s_seg[i]], cbn, lane);
     } else {
         copy_rows(0, ti.nrows, 0, ti.ncols * ES / 16);
         sync_stores();
@@ -326,10 +399,10 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
                 // destination and in one or more of its fence groups
                 const int i = base + lane;
                 const bool active = i < nseg;
-                int f0 = 0, fb = 0, fe = 0, gs = 1, g_first = 0, g_last = -1, gid0 = 0;
+                int f0 = 0, fb = 0, fe = 0, gs = 1, g_first = 0, g_last = -1, gid0 = 0, dst = 0;
                 if (active) {
                     const int r0 = s_seg[i];
-                    const int dst = s_dest[r0];
+                    dst = s_dest[r0];
                     fb = a.dest_flag_begin[dst];
                     fe = a.dest_flag_begin[dst + 1];
                     f0 = a.slot_flag[s_slot[r0]] + cb0;
@@ -364,6 +437,7 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
                             __hip_atomic_store(&a.group_counter[gi], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         n_fence += 1;
                         n_flag += (u64)(ge - gb);
+                        if (a.dest_done) ready_flags_stored(a, __shfl(dst, src, 64), ge - gb, lane);
                     }
                 }
             }
@@ -413,17 +487,25 @@ __device__ __forceinline__ void g2_tile(const KArgs &a, const TileInfo &ti, char
 struct StageLds {  // broadcast slots of a stage's task loop, in dynamic LDS at KArgs::sched_lds_off
     int next, ok;
     int pick;  // tile stage: the list to draw from next, -1 = all lists are empty
+    int q, hops, ticket, g1_left;  // ready-queue scheduler: the workgroup's state (see ready_queue_stage)
 };
 
 // One kind of tile (GEMM1 if GATED, else GEMM2; big or SMALL row blocks) from the eight tile
-// queues, the one of XCD `home` first, until none is left.
+// queues, the one of XCD `home` first, until none is left; or, when one_a >= 0, exactly one
+// tile that the caller has taken already: entry one_b of list one_a (GEMM1), or row block
+// one_a of this kind, column tile one_b (GEMM2, whose rows of h are known to be complete).
+// In that case, if ticket_q >= 0, a ticket of ready queue ticket_q is drawn where the list
+// mode draws its next tile, and left in StageLds::next (0x7fffffff: none drawn).
 template <class P, bool GATED, bool SMALL>
 static __device__ __attribute__((noinline)) void tile_stage(KArgsAddr args, u32 smem_off, int home, int n_rb, int n_rbs,
+                                                           int one_a, int one_b, int ticket_q,
                                                            volatile int *caller_local) {
     KArgs a = load_kernel_args(args);
     mark_global(a);
     char *smem = lds_at((u32)uniform((int)smem_off));
     home = uniform(home), n_rb = uniform(n_rb), n_rbs = uniform(n_rbs);
+    one_a = uniform(one_a), one_b = uniform(one_b), ticket_q = uniform(ticket_q);
+    const bool single = one_a >= 0;
     const int tid = threadIdx.x;
     Ctrl *c = a.ctrl;
     StageLds *sl = (StageLds *)(smem + a.sched_lds_off);
@@ -431,47 +513,72 @@ static __device__ __attribute__((noinline)) void tile_stage(KArgsAddr args, u32 
     const u64 t0 = kernel_start_ticks(c);
     constexpr int LIST = (GATED ? 0 : 2) + (SMALL ? 1 : 0);
     *caller_local = LIST;  // (see the call sites)
-    while (true) {
-        // one look at the eight counters of this kind picks the first list, from this XCD's on, that
-        // still has entries (a draw from an empty list costs a trip to memory and two barriers)
-        __syncthreads();
-        if (tid < 64) {
-            bool has = false;
-            if (tid < kTileQueues) {
-                const int qq = (home + tid) % kTileQueues;
-                const TileQueue t2 = tile_queue(a, n_rb, n_rbs, qq);
-                const int n2 = GATED ? (SMALL ? t2.n1s : t2.n1b) : (SMALL ? t2.n2s : t2.n2b);
-                has = ld_relaxed_agent(&c->tile_next[LIST][qq]) < (u32)n2;
+    bool more = true;
+    while (more) {
+        int q, n, i;
+        u32 *counter;
+        if (single) {
+            more = false;
+            q = GATED ? one_a : 0;
+            i = GATED ? one_b : 0;
+            n = i + 1;
+            counter = &c->rq_head[ticket_q >= 0 ? ticket_q : 0];
+        } else {
+            // one look at the eight counters of this kind picks the first list, from this XCD's on, that
+            // still has entries (a draw from an empty list costs a trip to memory and two barriers)
+            __syncthreads();
+            if (tid < 64) {
+                bool has = false;
+                if (tid < kTileQueues) {
+                    const int qq = (home + tid) % kTileQueues;
+                    const TileQueue t2 = tile_queue(a, n_rb, n_rbs, qq);
+                    const int n2 = GATED ? (SMALL ? t2.n1s : t2.n1b) : (SMALL ? t2.n2s : t2.n2b);
+                    has = ld_relaxed_agent(&c->tile_next[LIST][qq]) < (u32)n2;
+                }
+                const u64 m = __ballot(has);
+                if (tid == 0) sl->pick = m ? (home + __ffsll((long long)m) - 1) % kTileQueues : -1;
             }
-            const u64 m = __ballot(has);
-            if (tid == 0) sl->pick = m ? (home + __ffsll((long long)m) - 1) % kTileQueues : -1;
+            __syncthreads();
+            q = uniform(sl->pick);
+            if (q < 0) break;
+            const TileQueue tq0 = tile_queue(a, n_rb, n_rbs, q);
+            n = GATED ? (SMALL ? tq0.n1s : tq0.n1b) : (SMALL ? tq0.n2s : tq0.n2b);
+            counter = &c->tile_next[LIST][q];
+            __syncthreads();
+            if (tid == 0) sl->next = (int)atomicAdd(counter, 1u);
+            __syncthreads();
+            i = uniform(sl->next);
         }
-        __syncthreads();
-        const int q = uniform(sl->pick);
-        if (q < 0) break;
         const TileQueue tq = tile_queue(a, n_rb, n_rbs, q);
-        const int n = GATED ? (SMALL ? tq.n1s : tq.n1b) : (SMALL ? tq.n2s : tq.n2b);
-        u32 *counter = &c->tile_next[LIST][q];
-        __syncthreads();
-        if (tid == 0) sl->next = (int)atomicAdd(counter, 1u);
-        __syncthreads();
-        int i = uniform(sl->next);
         while (i < n) {
             // the next entry is drawn after this tile's main loop and consumed at the end of the tile
             u32 next = 0x7fffffffu;
             auto draw = [&]() {
-                if (tid == 0) next = atomicAdd(counter, 1u);
+                if ((!single || ticket_q >= 0) && tid == 0) next = atomicAdd(counter, 1u);
             };
             MOE_TT_BEGIN();
             if (GATED) {
                 const TileInfo ti = decode_tile<SMALL>(a, tb, tq, i, a.tl.NT1, P::BN1, a.f);
                 MOE_TT(c, 0);
-                g1_tile<P>(a, ti, smem, draw);
+                const u32 before = g1_tile<P>(a, ti, smem, draw);
+                // ready-queue scheduler: the last GEMM1 tile of a row block enqueues the block's GEMM2
+                // tiles (every writer of the block released its rows before it was counted)
+                if (a.rq_slots && tid == 0 && before + 1 == (u32)a.tl.NT1) {
+                    const int rq = SMALL ? ready_queue_of_block(n_rbs, ti.rb - n_rb) : ready_queue_of_block(n_rb, ti.rb);
+                    const u32 base = atomicAdd(&c->rq_tail[rq], (u32)a.tl.NT2);
+                    u32 *slots = a.rq_slots + (size_t)rq * a.rq_cap;
+                    for (int j = 0; j < a.tl.NT2; ++j)
+                        if (base + j < (u32)a.rq_cap) st_relaxed(&slots[base + j], 1u + (u32)ti.rb * a.tl.NT2 + j, 0);
+                }
                 MOE_TT(c, 4);
             } else {
-                const TileInfo ti = decode_tile<SMALL>(a, tb, tq, i, a.tl.NT2, P::BN2, a.d);
+                const TileInfo ti = single ? decode_block_tile<SMALL>(a, tb, one_a, one_b, P::BN2, a.d)
+                                           : decode_tile<SMALL>(a, tb, tq, i, a.tl.NT2, P::BN2, a.d);
                 // h rows are written once, by GEMM1 tiles that released them before counting themselves
-                if (tid == 0) sl->ok = wait_ge<false>(c, &a.h_ready[ti.rb], (u32)a.tl.NT1) ? 1 : 0;
+                if (tid == 0) {
+                    sl->ok = (single || wait_ge<false>(c, &a.h_ready[ti.rb], (u32)a.tl.NT1)) ? 1 : 0;
+                }
+                if (single) fence_acquire_no_invalidate();
                 __syncthreads();
                 MOE_TT(c, 5);
                 if (sl->ok)
@@ -671,6 +778,131 @@ __device__ __forceinline__ void combine_stage(const KArgs &a, char *smem) {
         __syncthreads();
         t = uniform(sl->next);
     }
+}
+
+// ---- the ready-queue scheduler (MOE_SCHED_READY_QUEUE; paper section 2.3: tasks are
+// enqueued when the data they need has arrived and processors take them from the queue).
+// After the front stage a workgroup holds at most one ticket of a ready queue (its own XCD's
+// until that queue's tickets are used up, then the next one's) and loops: if the entry of its
+// ticket has been written, run it (a GEMM2 tile or a combine task) and draw the next ticket
+// while it runs; else run a GEMM1 tile (big before small, own XCD's list first); else sleep.
+// So ready tasks go before new GEMM1 tiles, GEMM2 tiles and combine tasks start in the order
+// in which their inputs became complete, and nothing that runs ever waits.  No deadlock,
+// whatever the grid size: a workgroup sleeps only when every GEMM1 tile has been handed out,
+// and then every entry still to be written will be written by a workgroup that is running a
+// tile; every ticket below the queue's size is held by a workgroup that runs its entry as
+// soon as it can.  A workgroup leaves when all queues are out of tickets and no GEMM1 tile
+// is left (or the error flag is up; the sleep is bounded like every wait here).
+template <class P, class PS, bool MIXED>
+__device__ __forceinline__ void ready_queue_stage(const KArgs &a, KArgsAddr kargs, char *smem, int home, int n_rb,
+                                                  int n_rbs, volatile int *caller_local) {
+    using ET = typename P::ET;
+    const int tid = threadIdx.x;
+    Ctrl *c = a.ctrl;
+    StageLds *sl = (StageLds *)(smem + a.sched_lds_off);
+    const u32 lds = lds_offset(smem);
+    const u64 t0 = kernel_start_ticks(c);
+    int q = home, hops = 0;  // the queue tickets come from; hops == kTileQueues: all queues are used up
+    int ticket = -1;         // entry of queue q this workgroup is to run (may lie beyond the queue's size), -1 = none
+    int g1_left = 1;
+    u64 idle_since = 0;      // thread 0: start of the current sleep, 0 = not sleeping
+    while (true) {
+        __syncthreads();
+        if (tid < 64) {
+            // lanes 0-7: big GEMM1 list of XCD home + lane; 8-15: its small one; 24: error flag
+            const int kind = tid >> 3, qq = (home + (tid & 7)) % kTileQueues;
+            bool has = false;
+            if (g1_left && (kind == 0 || (kind == 1 && MIXED))) {
+                const TileQueue tq = tile_queue(a, n_rb, n_rbs, qq);
+                has = ld_relaxed_agent(&c->tile_next[kind][qq]) < (u32)(kind == 0 ? tq.n1b : tq.n1s);
+            } else if (tid == 24) {
+                has = ld_relaxed_agent(&c->error) != 0u;
+            }
+            const u64 m = __ballot(has);
+            if (tid == 0) {
+                // a ticket beyond its queue's size says the queue is used up: on to the next one
+                if (ticket >= 0 && ticket >= ready_queue_size(a, n_rb, n_rbs, q)) ticket = -1, q = (q + 1) % kTileQueues, ++hops;
+                while (ticket < 0 && hops < kTileQueues) {
+                    ticket = (int)atomicAdd(&c->rq_head[q], 1u);
+                    if (ticket >= ready_queue_size(a, n_rb, n_rbs, q)) ticket = -1, q = (q + 1) % kTileQueues, ++hops;
+                }
+                u32 *slot = &a.rq_slots[(size_t)q * a.rq_cap + (ticket >= 0 ? ticket : 0)];
+                const u32 v = ticket >= 0 ? ld_relaxed_agent(slot) : 0u;
+                int pick = 0, val = 0, lq = 0;  // pick: -2 leave, 0 sleep, 1 ready task, 2 / 3 big / small GEMM1 tile, 4 look again
+                if ((m >> 24) & 1ull) {
+                    pick = -2;
+                } else if (v != 0u) {
+                    st_relaxed(slot, 0u, 0);  // empty again for the next call
+                    ticket = -1;
+                    atomicAdd(&c->stats[16], 1ull);
+                    // out of order: a GEMM2 tile goes first although GEMM1 tiles are still in the lists
+                    if (!(v & kReadyCombine) && (m & 0xffffull)) atomicAdd(&c->stats[17], 1ull);
+                    pick = 1, val = (int)v;
+                } else if (m & 0xffffull) {
+                    const u32 lists = (u32)(m & 0xffffull);
+                    const int kd = (lists & 0xffu) ? 0 : 1;
+                    lq = (home + __ffs((int)((lists >> (8 * kd)) & 0xffu)) - 1) % kTileQueues;
+                    const TileQueue tq = tile_queue(a, n_rb, n_rbs, lq);
+                    const u32 i = atomicAdd(&c->tile_next[kd][lq], 1u);
+                    pick = (i < (u32)(kd == 0 ? tq.n1b : tq.n1s)) ? 2 + kd : 4;
+                    val = (int)i;
+                } else {
+                    g1_left = 0;
+                    if (ticket < 0) pick = -2;  // hops == kTileQueues: nothing more can come
+                }
+                if (pick == 0) {
+                    const u64 now = now_ticks();
+                    if (idle_since == 0) idle_since = now;
+                    if (now - idle_since > kWaitTicks) {
+                        set_error(c, MOE_ERR_TIMEOUT);
+                        atomicAdd(&c->stats[6], 1ull);
+                        pick = -2;
+                    }
+                } else if (idle_since != 0) {
+                    atomicAdd(&c->stats[14], now_ticks() - idle_since);
+                    idle_since = 0;
+                }
+                sl->pick = pick, sl->next = val, sl->ok = lq;
+                sl->q = q, sl->hops = hops, sl->ticket = ticket, sl->g1_left = g1_left;
+            }
+        }
+        __syncthreads();
+        const int pick = uniform(sl->pick), val = uniform(sl->next), lq = uniform(sl->ok);
+        q = uniform(sl->q), hops = uniform(sl->hops), ticket = uniform(sl->ticket), g1_left = uniform(sl->g1_left);
+        if (pick == -2) break;
+        if (pick == 0) __builtin_amdgcn_s_sleep(8);
+        if (pick == 0 || pick == 4) continue;
+        // the next ticket is drawn while the task runs, if the workgroup holds none
+        int tq_next = (ticket < 0 && hops < kTileQueues) ? q : -1;
+        if ((pick == 3 && !MIXED) || (pick == 1 && !((u32)val & kReadyCombine) && (val - 1) / a.tl.NT2 >= n_rb && !MIXED))
+            tq_next = -1;  // (cannot happen: no such tiles without mixed heights; nothing runs, nothing is drawn)
+        if (pick == 2) {
+            tile_stage<P, true, false>(kargs, lds, home, n_rb, n_rbs, lq, val, tq_next, caller_local);
+        } else if (pick == 3) {
+            if (MIXED) tile_stage<PS, true, true>(kargs, lds, home, n_rb, n_rbs, lq, val, tq_next, caller_local);
+        } else if ((u32)val & kReadyCombine) {
+            u32 next = 0x7fffffffu;
+            if (tid == 0 && tq_next >= 0) next = atomicAdd(&c->rq_head[tq_next], 1u);
+            combine_task<ET, true>(a, (int)((u32)val & ~kReadyCombine));
+            __syncthreads();
+            if (tid == 0) {
+                mark_phase_end(c, 5, t0);
+                sl->next = (int)next;
+            }
+        } else {
+            const int code = val - 1, rb = code / a.tl.NT2, ct = code % a.tl.NT2;
+            if (rb < n_rb)
+                tile_stage<P, false, false>(kargs, lds, home, n_rb, n_rbs, rb, ct, tq_next, caller_local);
+            else if (MIXED)
+                tile_stage<PS, false, true>(kargs, lds, home, n_rb, n_rbs, rb - n_rb, ct, tq_next, caller_local);
+        }
+        __syncthreads();
+        if (tq_next >= 0) {
+            const int t = uniform(sl->next);
+            if (t != 0x7fffffff) ticket = t;
+        }
+    }
+    if (tid == 0 && idle_since != 0) atomicAdd(&c->stats[14], now_ticks() - idle_since);
 }
 
 }  // namespace moe

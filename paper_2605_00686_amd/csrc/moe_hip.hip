@@ -207,24 +207,29 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
         // callee-saved registers in these functions (they have one caller, which keeps nothing in them):
         // some 270 registers per lane through scratch memory, per call, otherwise.
         volatile int stage_mark = 0;
-        MOE_TT_BEGIN();
-        tile_stage<P, true, false>(kargs, lds, home, n_rb, n_rbs, &stage_mark);
-        MOE_TT(c, 20);
-        if (MIXED && n_rbs > 0) tile_stage<PS, true, true>(kargs, lds, home, n_rb, n_rbs, &stage_mark);
-        MOE_TT(c, 21);
-        tile_stage<P, false, false>(kargs, lds, home, n_rb, n_rbs, &stage_mark);
-        MOE_TT(c, 22);
-        if (MIXED && n_rbs > 0) tile_stage<PS, false, true>(kargs, lds, home, n_rb, n_rbs, &stage_mark);
-        MOE_TT(c, 23);
+        if (a.scheduler == MOE_SCHED_READY_QUEUE) {
+            // ---- stages 2 and 3 from the ready queues
+            ready_queue_stage<P, PS, MIXED>(a, kargs, smem, home, n_rb, n_rbs, &stage_mark);
+        } else {
+            MOE_TT_BEGIN();
+            tile_stage<P, true, false>(kargs, lds, home, n_rb, n_rbs, -1, -1, -1, &stage_mark);
+            MOE_TT(c, 20);
+            if (MIXED && n_rbs > 0) tile_stage<PS, true, true>(kargs, lds, home, n_rb, n_rbs, -1, -1, -1, &stage_mark);
+            MOE_TT(c, 21);
+            tile_stage<P, false, false>(kargs, lds, home, n_rb, n_rbs, -1, -1, -1, &stage_mark);
+            MOE_TT(c, 22);
+            if (MIXED && n_rbs > 0) tile_stage<PS, false, true>(kargs, lds, home, n_rb, n_rbs, -1, -1, -1, &stage_mark);
+            MOE_TT(c, 23);
 #ifdef MOE_TILE_TIMING
-        if (tid == 0) {
-            const u64 t = now_ticks() - c->t0;
-            atomicAdd(&c->dbg[14], t);
-            atomicMax(&c->dbg[15], t);
-        }
+            if (tid == 0) {
+                const u64 t = now_ticks() - c->t0;
+                atomicAdd(&c->dbg[14], t);
+                atomicMax(&c->dbg[15], t);
+            }
 #endif
-        // ---- stage 3: combine
-        combine_stage<ET>(a, smem);
+            // ---- stage 3: combine
+            combine_stage<ET>(a, smem);
+        }
     }
     // last workgroup out copies the statistics and clears the control block
     sync_stores();
@@ -289,7 +294,9 @@ struct Plan {
     int kind;
     Tiling tl;
     // workspace byte offsets
-    size_t o_ctrl, o_blk_hist, o_seg_cnt, o_group_counter, o_h_ready, zero_bytes;
+    size_t o_ctrl, o_blk_hist, o_seg_cnt, o_group_counter, o_h_ready, o_dest_done, zero_bytes;
+    size_t o_rq_slots, init_zero_bytes;  // the ready queues empty themselves: zeroed by moe_workspace_init only
+    int rq_cap;
     size_t o_blk_base, o_seg_begin, o_flag_base, o_dest_flag_begin, o_dest_group_begin, o_rb_base, o_rb_expert, o_rbs_base, o_rbs_expert, o_h, o_wgt, total;
 };
 
@@ -302,6 +309,7 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     if (p->fence_scope != MOE_SCOPE_AGENT && p->fence_scope != MOE_SCOPE_SYSTEM) return MOE_ERR_INVALID_ARG;
     if (p->tile_m < 0 || p->tile_n < 0) return MOE_ERR_INVALID_ARG;
     if (p->group_size < 0 || (p->group_size != 0 && p->signal_mode != MOE_SIGNAL_PER_DEST)) return MOE_ERR_INVALID_ARG;
+    if (p->scheduler != MOE_SCHED_STATIC && p->scheduler != MOE_SCHED_READY_QUEUE) return MOE_ERR_INVALID_ARG;
     if (p->E > kMaxExperts || p->k > 32 || p->R > kMaxDest) return MOE_ERR_UNSUPPORTED;
     if ((long long)p->T * p->k > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
     const int tm = p->tile_m ? p->tile_m : 128, tn = p->tile_n ? p->tile_n : 64;
@@ -319,6 +327,8 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     pl->nPB = (p->T + kPermBlock - 1) / kPermBlock;
     pl->nRT = (p->T + kRouteTokens - 1) / kRouteTokens;
     pl->comb_tokens = p->T >= 16384 ? 16 : p->T >= 8192 ? 8 : p->T >= 2048 ? 4 : 1;
+    // the ready-queue scheduler enqueues combine tasks per destination: none may span two
+    if (p->scheduler == MOE_SCHED_READY_QUEUE && pl->per_dest % pl->comb_tokens != 0) pl->comb_tokens = 1;
     pl->nCT = (p->T + pl->comb_tokens - 1) / pl->comb_tokens;
     // tile shape: the smallest row block that holds an average expert, never
     // smaller than the publish tile (a publish tile must not span two compute tiles)
@@ -353,12 +363,20 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     pl->o_ctrl = take(sizeof(Ctrl));
     pl->o_blk_hist = take((size_t)pl->nPB * p->E * 4);
     pl->o_seg_cnt = take((size_t)p->E * p->R * 4);
-    // fence groups: one per destination, or at most flags / g + R of them
-    const size_t max_flags = ((size_t)(pl->N + tm - 1) / tm + (size_t)p->E * p->R) * pl->ncb;
-    const size_t max_groups = p->group_size > 0 ? max_flags / p->group_size + p->R : (size_t)p->R;
-    pl->o_group_counter = take(max_groups * 4);
     pl->o_h_ready = take((size_t)pl->maxRB_layout * 4);
+    pl->o_dest_done = take((size_t)p->R * 4);
     pl->zero_bytes = o;
+    // What follows is zero between calls because its users leave it so (moe_workspace_init zeroes it
+    // once).  Sizes are the largest any signal mode, group size or scheduler needs, so that the
+    // layout depends on the shape of the problem only and these may change from call to call.
+    // Fence groups: one counter per group, at most one group per flag (group_size 1) plus R.
+    const size_t max_flags = ((size_t)(pl->N + tm - 1) / tm + (size_t)p->E * p->R) * pl->ncb;
+    pl->o_group_counter = take((max_flags + p->R) * 4);
+    // One ready queue per XCD, each able to hold every GEMM2 tile and every combine task (at most
+    // one per token).
+    pl->rq_cap = (pl->tl.maxRB + p->E) * pl->tl.NT2 + p->T;
+    pl->o_rq_slots = take((size_t)kTileQueues * pl->rq_cap * 4);
+    pl->init_zero_bytes = o;
     pl->o_blk_base = take((size_t)pl->nPB * p->E * 4);
     pl->o_seg_begin = take((size_t)p->E * p->R * 4);
     pl->o_flag_base = take((size_t)p->E * p->R * 4);
@@ -382,6 +400,7 @@ static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
     a->dtype = p.dtype; a->tile_m = pl.tile_m; a->tile_n = pl.tile_n;
     a->signal_mode = p.signal_mode; a->fence_scope = p.fence_scope; a->epoch = p.epoch;
     a->group_size = p.group_size;
+    a->scheduler = p.scheduler;
     a->N = pl.N; a->per_dest = pl.per_dest; a->ncb = pl.ncb;
     a->nPB = pl.nPB; a->nRT = pl.nRT; a->nCT = pl.nCT; a->comb_tokens = pl.comb_tokens;
     a->seg_from_blocks = (pl.per_dest % kPermBlock == 0) ? 1 : 0;
@@ -398,6 +417,11 @@ static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
         a->seg_cnt = (int32_t *)(ws + pl.o_seg_cnt);
         a->group_counter = (u32 *)(ws + pl.o_group_counter);
         a->h_ready = (u32 *)(ws + pl.o_h_ready);
+        if (p.scheduler == MOE_SCHED_READY_QUEUE) {
+            a->dest_done = (u32 *)(ws + pl.o_dest_done);
+            a->rq_slots = (u32 *)(ws + pl.o_rq_slots);
+            a->rq_cap = pl.rq_cap;
+        }
         a->blk_base = (int32_t *)(ws + pl.o_blk_base);
         a->seg_begin = (int32_t *)(ws + pl.o_seg_begin);
         a->flag_base = (int32_t *)(ws + pl.o_flag_base);
@@ -500,7 +524,7 @@ int moe_workspace_init(const moe_problem_t *p, void *workspace, void *stream) {
     int rc = make_plan(p, &pl);
     if (rc) return rc;
     if ((rc = check_ws(workspace))) return rc;
-    hipLaunchKernelGGL(k_zero, dim3(64), dim3(kThreads), 0, (hipStream_t)stream, (u32 *)workspace, pl.zero_bytes / 4);
+    hipLaunchKernelGGL(k_zero, dim3(64), dim3(kThreads), 0, (hipStream_t)stream, (u32 *)workspace, pl.init_zero_bytes / 4);
     return hip_ok(hipGetLastError());
 }
 

@@ -21,15 +21,15 @@ def _dev(inp, names):
     return {n: (inp[n].cuda() if inp.get(n) is not None else None) for n in names}
 
 
-def _problem(B, cfg, signal_mode=1, fence_scope=0, epoch=1, group_size=0):
+def _problem(B, cfg, signal_mode=1, fence_scope=0, epoch=1, group_size=0, scheduler=0):
     return B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
                      tile_n=cfg["tile_n"], signal_mode=signal_mode, fence_scope=fence_scope, epoch=epoch,
-                     group_size=group_size)
+                     group_size=group_size, scheduler=scheduler)
 
 
-def run_forward(B, inp, signal_mode, fence_scope, epoch=1, buf=None, group_size=0):
+def run_forward(B, inp, signal_mode, fence_scope, epoch=1, buf=None, group_size=0, scheduler=0):
     cfg = inp["cfg"]
-    p = _problem(B, cfg, signal_mode, fence_scope, epoch, group_size)
+    p = _problem(B, cfg, signal_mode, fence_scope, epoch, group_size, scheduler)
     buf = buf or B.Buffers(p)
     d = _dev(inp, ("x", "Wg", "gate_bias", "W1", "W3", "W2"))
     if cfg["prerouted"] is not None:
@@ -106,6 +106,30 @@ def test_megakernel_fence_group_size(name):
             buf = B.Buffers(_problem(B, inp["cfg"], 1, 0, 1, group_size=1))
         p, buf = run_forward(B, inp, 1, 0, epoch=epoch, buf=buf, group_size=g)
         ref = check_against_oracle(B, inp, p, buf, 1, ref)
+
+
+@pytest.mark.parametrize("name", ["mini_f32", "mini_bf16", "mini_skew", "mini_pre", "mini_decode", "mini_large", "mini_odd"])
+def test_megakernel_ready_queue_scheduler(name):
+    """The ready-queue scheduler (section 2.3: tasks enqueued when their inputs are there) against the
+    oracle, in both signaling modes and with fence groups, on one set of buffers with rising epochs (so
+    every queue must have emptied itself for the next call).  Every GEMM2 tile and every combine task
+    goes through a queue exactly once."""
+    B = _binding()
+    inp = W.make_inputs(name)
+    buf = B.Buffers(_problem(B, inp["cfg"], 1, 0, 1, group_size=1, scheduler=1))
+    ref = None
+    for epoch, (mode, g) in enumerate([(1, 0), (0, 0), (1, 5), (1, 0)], start=2):
+        print(f"case {name} ready queue, signal_mode {mode} group_size {g}", flush=True)
+        p, buf = run_forward(B, inp, mode, 0, epoch=epoch, buf=buf, group_size=g, scheduler=1)
+        ref = check_against_oracle(B, inp, p, buf, mode, ref)
+        stats = buf.stats.cpu().numpy()
+        n_comb = int(stats[16]) - int(stats[5])  # combine tasks: equal shares of every destination's tokens
+        cfg = inp["cfg"]
+        assert n_comb >= cfg["R"] and (cfg["T"] // cfg["R"]) % (n_comb // cfg["R"]) == 0 and n_comb % cfg["R"] == 0, stats.tolist()
+    # and the static scheduler again on the same workspace
+    p, buf = run_forward(B, inp, 1, 0, epoch=9, buf=buf, group_size=0, scheduler=0)
+    check_against_oracle(B, inp, p, buf, 1, ref)
+    assert buf.stats.cpu().numpy()[16] == 0
 
 
 def test_megakernel_gate_many_experts_and_ties():
