@@ -16,13 +16,13 @@ pytestmark = pytest.mark.gpu
 SAMPLES = {"cfg1": 256, "cfg2": 48, "cfg3": 48, "cfg4": 12, "cfg5": 24, "cfg6": 24}
 
 
-def _run(name, signal_mode, fence_scope, inp=None, buf=None, epoch=1, group_size=0):
+def _run(name, signal_mode, fence_scope, inp=None, buf=None, epoch=1, group_size=0, scheduler=0):
     from paper_2605_00686_amd import binding as B
     inp = inp or W.make_inputs(name)
     cfg = inp["cfg"]
     p = B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
                   tile_n=cfg["tile_n"], signal_mode=signal_mode, fence_scope=fence_scope, epoch=epoch,
-                  group_size=group_size)
+                  group_size=group_size, scheduler=scheduler)
     buf = buf or B.Buffers(p)
     dev = inp.setdefault("_dev", {n: (inp[n].cuda() if inp[n] is not None else None)
                                   for n in ("x", "Wg", "gate_bias", "W1", "W3", "W2")})
@@ -93,5 +93,11 @@ def test_fullsize_parity(name):
         for epoch, (mode, scope) in enumerate([(1, 1), (0, 1)], start=3):
             B, inp, p, buf = _run(name, mode, scope, inp=inp, buf=buf, epoch=epoch)
             _check(B, inp, p, buf, mode, name, cache)
-        B, inp, p, buf = _run(name, 1, 0, inp=inp, epoch=5, group_size=16)  # (its own, larger workspace)
+        B, inp, p, buf = _run(name, 1, 0, inp=inp, buf=buf, epoch=5, group_size=16)
         _check(B, inp, p, buf, 1, name, cache)
+    # the ready-queue scheduler on the same buffers, then the default again
+    B, inp, p, buf = _run(name, 1, 0, inp=inp, buf=buf, epoch=6, scheduler=1)
+    _check(B, inp, p, buf, 1, name, cache)
+    assert buf.stats.cpu().numpy()[16] > 0
+    B, inp, p, buf = _run(name, 1, 0, inp=inp, buf=buf, epoch=7)
+    _check(B, inp, p, buf, 1, name, cache)

@@ -99,11 +99,10 @@ def test_megakernel_fence_group_size(name):
     B = _binding()
     inp = W.make_inputs(name)
     ref, buf = None, None
-    for epoch, g in enumerate([1, 3, 8, 64, 100000, 0], start=2):
+    for epoch, g in enumerate([0, 3, 1, 64, 100000, 8, 0], start=2):
         print(f"case {name} group_size {g}", flush=True)
-        # the workspace depends on g (number of group counters): keep the largest, which is g = 1, from the start
-        if buf is None:
-            buf = B.Buffers(_problem(B, inp["cfg"], 1, 0, 1, group_size=1))
+        if buf is None:  # (one workspace serves every granularity)
+            buf = B.Buffers(_problem(B, inp["cfg"], 1, 0, 1))
         p, buf = run_forward(B, inp, 1, 0, epoch=epoch, buf=buf, group_size=g)
         ref = check_against_oracle(B, inp, p, buf, 1, ref)
 
@@ -116,7 +115,7 @@ def test_megakernel_ready_queue_scheduler(name):
     goes through a queue exactly once."""
     B = _binding()
     inp = W.make_inputs(name)
-    buf = B.Buffers(_problem(B, inp["cfg"], 1, 0, 1, group_size=1, scheduler=1))
+    buf = B.Buffers(_problem(B, inp["cfg"], 1, 0, 1))
     ref = None
     for epoch, (mode, g) in enumerate([(1, 0), (0, 0), (1, 5), (1, 0)], start=2):
         print(f"case {name} ready queue, signal_mode {mode} group_size {g}", flush=True)
