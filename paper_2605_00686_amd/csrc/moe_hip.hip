@@ -81,6 +81,9 @@ __device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
                 fence_release(0);
                 atomicAdd(&c->wgt_done, 1u);
             }
+#ifdef MOE_TILE_TIMING
+            if (tid == 0) atomicMax(&c->dbg[46], now_ticks() - c->t0);
+#endif
         } else if (task < a.t_plan) {
             phase = 0;
             if (a.t_gate > 0 && !seen_wgt) {  // the transposed gate weights are complete
@@ -88,6 +91,9 @@ __device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
                 __syncthreads();
                 seen_wgt = true;
                 bad = bad || !sl->ok;
+#ifdef MOE_TILE_TIMING
+                if (tid == 0) atomicMax(&c->dbg[45], now_ticks() - c->t0);
+#endif
             }
             if (!bad) route_task<ET>(a, task - a.t_gate, smem, true);
             sync_stores();
@@ -263,6 +269,7 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
             printf("screened gate (us/task): screen %.2f, candidates %.2f, exact %.2f, select %.2f; fallbacks %llu\n",
                    c->dbg[40] / (double)a.nRT / 100., c->dbg[41] / (double)a.nRT / 100., c->dbg[42] / (double)a.nRT / 100.,
                    c->dbg[43] / (double)a.nRT / 100., c->dbg[44]);
+            printf("last transposition task ends at %.2f us, last gate task starts at %.2f us; ", c->dbg[46] / 100., c->dbg[45] / 100.);
             printf("plan starts at %.2f us; ", c->dbg[39] / 100.);
             printf("plan (us): stage %.2f, expert scans %.2f, block scan %.2f, flags %.2f, write-back %.2f\n", c->dbg[34] / 100.,
                    c->dbg[35] / 100., c->dbg[36] / 100., c->dbg[37] / 100., c->dbg[38] / 100.);

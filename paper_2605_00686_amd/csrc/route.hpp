@@ -267,6 +267,37 @@ __device__ __forceinline__ void wgt_task(const KArgs &a, int task, char *smem) {
     bf16_t *tile = (bf16_t *)smem;    // [64 k][LD]
     const bf16_t *Wg = (const bf16_t *)a.Wg;
     bf16_t *WgT = (bf16_t *)a.WgT;
+    if ((E & 7) == 0) {
+        // 16-byte pieces both ways, all loads of a thread in flight together: this task sits in front of
+        // every gate task, so its latency is the kernel's
+        constexpr int PPT = kWgtTile * kWgtTile / 8 / kThreads;  // pieces per thread
+        u32x4_t v[PPT];
+#pragma unroll
+        for (int u = 0; u < PPT; ++u) {
+            const int q = tid + kThreads * u, kk = q >> 3, e = e0 + (q & 7) * 8;
+            v[u] = u32x4_t{0u, 0u, 0u, 0u};
+            if (e < E) v[u] = *(const u32x4_t *)(Wg + (size_t)(k0 + kk) * E + e);
+        }
+#pragma unroll
+        for (int u = 0; u < PPT; ++u) {
+            const int q = tid + kThreads * u, kk = q >> 3, pc = q & 7;
+            u32 *dst = (u32 *)(tile + kk * LD + pc * 8);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dst[i] = v[u][i];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < PPT; ++u) {
+            const int q = tid + kThreads * u, ee = q >> 3, kp = (q & 7) * 8;
+            u32x4_t o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                o[i] = (u32)tile[(kp + 2 * i) * LD + ee] | ((u32)tile[(kp + 2 * i + 1) * LD + ee] << 16);
+            if (e0 + ee < E) *(u32x4_t *)(WgT + (size_t)(e0 + ee) * d + k0 + kp) = o;
+        }
+        __syncthreads();
+        return;
+    }
     for (int q = tid; q < kWgtTile * kWgtTile; q += kThreads) {
         const int kk = q / kWgtTile, ee = q % kWgtTile;
         tile[kk * LD + ee] = (e0 + ee < E) ? Wg[(size_t)(k0 + kk) * E + e0 + ee] : (bf16_t)0;

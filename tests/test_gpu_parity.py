@@ -131,19 +131,21 @@ def test_megakernel_ready_queue_scheduler(name):
     assert buf.stats.cpu().numpy()[16] == 0
 
 
-def test_megakernel_gate_many_experts_and_ties():
+@pytest.mark.parametrize("E", [96, 70])
+def test_megakernel_gate_many_experts_and_ties(E):
     """Gate with E >= 64 (the path that screens in bf16 and decides on exact fp64 logits of the
     candidates only).  Some rows of x are zero, so all 96 logits of those tokens are equal: more
     candidates than that path keeps, which sends the task down the exact path for all experts;
-    the tie-break (lower expert first, equal weights) must come out as the oracle's."""
+    the tie-break (lower expert first, equal weights) must come out as the oracle's.  E = 70: a row of
+    the gate weights is not a whole number of 16-byte pieces."""
     B = _binding()
-    cfg = dict(T=192, d=256, E=96, k=4, f=128, R=4, dtype="bf16", seed=21)
+    cfg = dict(T=192, d=256, E=E, k=4, f=128, R=4, dtype="bf16", seed=21)
     inp = W.make_inputs(cfg)
     inp["x"][5] = 0
     inp["x"][40:44] = 0
     inp["x"][191] = 0
     for mode in (1, 0):
-        print(f"case gate E=96 with ties, signal_mode {mode}", flush=True)
+        print(f"case gate E={E} with ties, signal_mode {mode}", flush=True)
         p, buf = run_forward(B, inp, mode, 0)
         check_against_oracle(B, inp, p, buf, mode)
     idx = buf.topk_idx.cpu().numpy()
