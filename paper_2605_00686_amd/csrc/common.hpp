@@ -157,6 +157,18 @@ __device__ __forceinline__ void fence_acquire_no_invalidate() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
+// 16-byte store of tile results (h, staging) that workgroups on other XCDs will read: written
+// through to memory.  An ordinary store would leave the line dirty in this XCD's L2 until the
+// release fence that follows the tile writes back everything dirty in that L2 at once, the other
+// workgroups' half-written tiles included; with write-through stores the fence finds little to do
+// (measured: 1.5 % of the whole layer on the two large workloads).  The instruction is written out
+// because no builtin sets these cache-policy bits on a 16-byte store; every caller follows its
+// stores with sync_stores(), which waits for them.
+__device__ __forceinline__ void store_tile16(char *p, const uint4 &v) {
+    const u32x4_t w = {v.x, v.y, v.z, v.w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(w));
+}
+
 // Workgroup barrier that also waits for this wavefront's outstanding global
 // stores.  __syncthreads() alone only drains LDS traffic; a store still in
 // flight when ANOTHER wavefront of the workgroup issues the release fence would

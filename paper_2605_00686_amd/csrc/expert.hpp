@@ -275,8 +275,8 @@ __device__ __forceinline__ u32 g1_tile(const KArgs &a, const TileInfo &ti, char 
     char *h = (char *)a.h;
     for (int q = threadIdx.x; q < ti.nrows * ppr; q += kThreads) {
         const int r = q / ppr, c = q % ppr;
-        *(uint4 *)(h + ((size_t)(ti.row0 + r) * a.f + ti.n0) * sizeof(ET) + c * 16) =
-            *(const uint4 *)(smem + r * P::C_STRIDE + c * 16);
+        store_tile16(h + ((size_t)(ti.row0 + r) * a.f + ti.n0) * sizeof(ET) + c * 16,
+                     *(const uint4 *)(smem + r * P::C_STRIDE + c * 16));
     }
     sync_stores();
     MOE_TT(a.ctrl, 2);
@@ -359,8 +359,8 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
         const int w = p1 - p0;
         for (int q = tid; q < (r1 - r0) * w; q += kThreads) {
             const int r = r0 + q / w, c = p0 + q % w;
-            *(uint4 *)(staging + ((size_t)s_slot[r] * a.d + ti.n0) * ES + c * 16) =
-                *(const uint4 *)(smem + r * P::C_STRIDE + c * 16);
+            store_tile16(staging + ((size_t)s_slot[r] * a.d + ti.n0) * ES + c * 16,
+                         *(const uint4 *)(smem + r * P::C_STRIDE + c * 16));
         }
     };
 
