@@ -55,7 +55,7 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
     int32_t *s_rb = s_dest + R + 1;    // [E+1] row blocks per expert, then their scan
     int32_t *s_grp = s_rb + E + 2;     // [R+1] fence groups per destination, then their scan
     int32_t *s_rbs = s_grp + R + 1;    // [E+1] small row blocks per expert (0 or 1), then their scan
-    int32_t *s_free = s_rbs + E + 2;
+    int32_t *s_free = s_cnt + ((4 * E + 2 * R + 7 + 3) & ~3);  // behind s_rbs, 16-byte aligned (inside the 12 spare words)
     MOE_TT_BEGIN();
     const bool seg_lds = plan_seg_in_lds(E, R), hist_lds = plan_hist_in_lds(nPB, E);
     int32_t *segc = a.seg_cnt, *segb = a.seg_begin, *hist = a.blk_base, *nfl = a.flag_base;
@@ -72,9 +72,17 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
         }
     }
     if (hist_lds) hist = s_free;
-    // (independent loads, several in flight per thread; blk_base <- blk_hist if not in LDS)
+    // (independent loads, all of a thread's in flight together: nothing else runs on the GPU while
+    // the plan does; blk_base <- blk_hist if not in LDS)
+    if (((nPB * E) & 3) == 0 && (!hist_lds || !seg_lds || ((3 * E * R) & 3) == 0)) {  // 16-byte pieces
+        const u32x4_t *src = (const u32x4_t *)a.blk_hist;
+        u32x4_t *dst = (u32x4_t *)hist;
 #pragma unroll 8
-    for (int q = tid; q < nPB * E; q += kThreads) hist[q] = a.blk_hist[q];
+        for (int q = tid; q < nPB * E / 4; q += kThreads) dst[q] = src[q];
+    } else {
+#pragma unroll 8
+        for (int q = tid; q < nPB * E; q += kThreads) hist[q] = a.blk_hist[q];
+    }
     __syncthreads();
     if (a.seg_from_blocks) {  // a destination is a whole number of blocks: add up its blocks' histograms
         const int bpd = a.per_dest / kPermBlock;
