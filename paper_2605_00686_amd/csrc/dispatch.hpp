@@ -227,11 +227,10 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
 // distinct, so the rank of slot (t, e) among the block's slots of e is the
 // number of earlier tokens of the block that chose e: a popcount on a 64-bit
 // per-expert mask.  Deterministic, no arrival-order atomics.
-template <typename ET>
-__device__ __forceinline__ void perm_task(const KArgs &a, int b, char *smem) {
+// mask[e] = the tokens of block b (bit = token - b*64) that chose expert e
+__device__ __forceinline__ void block_masks(const KArgs &a, int b, u64 *mask) {
     const int tid = threadIdx.x;
     const int E = a.E, k = a.k;
-    u64 *mask = (u64 *)smem;  // [E]
     const int t0 = b * kPermBlock;
     const int nt = min(kPermBlock, a.T - t0);
     for (int e = tid; e < E; e += kThreads) mask[e] = 0ull;
@@ -241,13 +240,24 @@ __device__ __forceinline__ void perm_task(const KArgs &a, int b, char *smem) {
         if (e >= 0 && e < E) atomicOr(&mask[e], 1ull << (q / k));
     }
     __syncthreads();
+}
+
+// base[e]: sorted position of the block's first slot of expert e (E entries, LDS or global)
+template <typename ET>
+__device__ __forceinline__ void perm_task(const KArgs &a, int b, char *smem, const int32_t *base) {
+    const int tid = threadIdx.x;
+    const int E = a.E, k = a.k;
+    u64 *mask = (u64 *)smem;  // [E]
+    const int t0 = b * kPermBlock;
+    const int nt = min(kPermBlock, a.T - t0);
+    block_masks(a, b, mask);
     for (int q = tid; q < nt * k; q += kThreads) {
         const int s = t0 * k + q;
         const int tl = q / k;
         const int e = a.idx[s];
         if (e < 0 || e >= E) continue;
         const int rank = __popcll(mask[e] & ((1ull << tl) - 1ull));
-        const int p = a.blk_base[(size_t)b * E + e] + rank;
+        const int p = base[e] + rank;
         a.perm[p] = s;
         a.inv_perm[s] = p;
         if (a.slot_flag) {
@@ -258,6 +268,66 @@ __device__ __forceinline__ void perm_task(const KArgs &a, int b, char *smem) {
         }
     }
     __syncthreads();
+}
+
+// Standalone dispatch without the single-workgroup plan (it needs none of the plan's tables for
+// tiles and flags), in two steps that every permutation block runs in parallel.
+// Step 1: the block's histogram = popcounts of its masks, to hist[b][.].
+__device__ __forceinline__ void block_hist_task(const KArgs &a, int b, int32_t *hist, char *smem) {
+    u64 *mask = (u64 *)smem;  // [E]
+    block_masks(a, b, mask);
+    for (int e = threadIdx.x; e < a.E; e += kThreads) hist[(size_t)b * a.E + e] = __popcll(mask[e]);
+}
+// LDS of step 2: all histograms, three tables of E + 1, the masks
+__host__ __device__ inline size_t block_perm_smem_bytes(int E, int nPB) {
+    return (((size_t)nPB * E + 3 * (E + 1)) * 4 + 15) / 16 * 16 + (size_t)E * 8;
+}
+// Step 2: every block reads all histograms (they are small), adds up the columns (counts), scans them
+// (offsets), takes the part of each column above itself (its base), and writes its slots' positions.
+// Block 0 also writes counts and offsets.
+template <typename ET>
+__device__ __forceinline__ void block_perm_task(const KArgs &a, int b, const int32_t *hist_g, char *smem) {
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int E = a.E, nPB = a.nPB;
+    int32_t *hist = (int32_t *)smem;   // [nPB][E]
+    int32_t *tot = hist + nPB * E;     // [E+1]
+    int32_t *base = tot + E + 1;       // [E+1]
+    int32_t *off = base + E + 1;       // [E+1]
+    char *mask_smem = smem + (((size_t)nPB * E + 3 * (E + 1)) * 4 + 15) / 16 * 16;
+    if (((nPB * E) & 3) == 0) {
+        const u32x4_t *src = (const u32x4_t *)hist_g;
+        u32x4_t *dst = (u32x4_t *)hist;
+#pragma unroll 8
+        for (int q = tid; q < nPB * E / 4; q += kThreads) dst[q] = src[q];
+    } else {
+#pragma unroll 8
+        for (int q = tid; q < nPB * E; q += kThreads) hist[q] = hist_g[q];
+    }
+    __syncthreads();
+    // column e, split over the four wavefronts' worth of threads when there are few experts
+    for (int e = tid; e < E; e += kThreads) {
+        int run = 0, mine = 0;
+        for (int bb = 0; bb < nPB; ++bb) {
+            if (bb == b) mine = run;
+            run += hist[bb * E + e];
+        }
+        tot[e] = run;
+        base[e] = mine;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const int total = wave_exclusive_scan(tot, off, E, 1, 0);
+        if (lane == 0) off[E] = total;
+    }
+    __syncthreads();
+    for (int e = tid; e < E; e += kThreads) base[e] += off[e];
+    if (b == 0)
+        for (int e = tid; e <= E; e += kThreads) {
+            a.offsets[e] = off[e];
+            if (e < E) a.counts[e] = tot[e];
+        }
+    __syncthreads();
+    perm_task<ET>(a, b, mask_smem, base);
 }
 
 // x_perm[p,:] = x[perm[p]/k,:] for sorted rows p = first, first+stride, ...: one

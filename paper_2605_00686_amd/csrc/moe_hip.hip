@@ -33,7 +33,19 @@ __global__ __launch_bounds__(kThreads) void k_plan(KArgs a) {
 template <typename ET>
 __global__ __launch_bounds__(kThreads) void k_perm(KArgs a) {
     extern __shared__ __align__(16) char smem[];
-    if (a.ctrl->error == 0) perm_task<ET>(a, blockIdx.x, smem);
+    if (a.ctrl->error == 0) perm_task<ET>(a, blockIdx.x, smem, a.blk_base + (size_t)blockIdx.x * a.E);
+}
+
+// standalone dispatch, short form (see block_hist_task): histograms go to blk_base, which nothing
+// else reads in this form, and nothing that must be zero between calls is touched
+__global__ __launch_bounds__(kThreads) void k_block_hist(KArgs a) {
+    extern __shared__ __align__(16) char smem[];
+    block_hist_task(a, blockIdx.x, a.blk_base, smem);
+}
+template <typename ET>
+__global__ __launch_bounds__(kThreads) void k_block_perm(KArgs a) {
+    extern __shared__ __align__(16) char smem[];
+    block_perm_task<ET>(a, blockIdx.x, a.blk_base, smem);
 }
 
 __global__ __launch_bounds__(kThreads) void k_gather(KArgs a, size_t row_bytes) {
@@ -122,7 +134,7 @@ __device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
                 seen_plan = true;
                 bad = bad || !sl->ok;
             }
-            if (!bad) perm_task<ET>(a, task - a.t_perm, smem);
+            if (!bad) perm_task<ET>(a, task - a.t_perm, smem, a.blk_base + (size_t)(task - a.t_perm) * a.E);
             sync_stores();
             if (tid == 0) {
                 fence_release(0);
@@ -569,6 +581,24 @@ int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx,
     a.x = x; a.idx = const_cast<int32_t *>(topk_idx);
     a.counts = counts; a.offsets = offsets; a.perm = perm; a.inv_perm = inv_perm; a.x_perm = x_perm;
     hipStream_t st = (hipStream_t)stream;
+    const size_t row_bytes = (size_t)p->d * elem_size(p->dtype);
+    int ggrid = (pl.N + 3) / 4;  // gather: one wavefront per row while rows last
+    if (ggrid > 8192) ggrid = 8192;
+    const size_t bsmem = block_perm_smem_bytes(p->E, pl.nPB);
+    if (bsmem <= 64 * 1024) {
+        // short form: per-block histograms, then every block derives its own base positions from all of
+        // them (no single-workgroup plan, whose tile and flag tables a dispatch alone does not need)
+        hipLaunchKernelGGL(k_block_hist, dim3(pl.nPB), dim3(kThreads), (size_t)p->E * 8, st, a);
+        if (p->dtype == MOE_DT_F32) {
+            if ((rc = set_smem(k_block_perm<float>, bsmem))) return rc;
+            hipLaunchKernelGGL(k_block_perm<float>, dim3(pl.nPB), dim3(kThreads), bsmem, st, a);
+        } else {
+            if ((rc = set_smem(k_block_perm<bf16_t>, bsmem))) return rc;
+            hipLaunchKernelGGL(k_block_perm<bf16_t>, dim3(pl.nPB), dim3(kThreads), bsmem, st, a);
+        }
+        if (x_perm) hipLaunchKernelGGL(k_gather, dim3(ggrid), dim3(kThreads), 0, st, a, row_bytes);
+        return hip_ok(hipGetLastError());
+    }
     const size_t psmem = plan_smem(pl);
     if ((rc = set_smem(k_plan, psmem))) return rc;
     // histogram (gate task without the gate), plan, permutation, row gather, clean-up
@@ -581,12 +611,7 @@ int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx,
         hipLaunchKernelGGL(k_plan, dim3(1), dim3(kThreads), psmem, st, a);
         hipLaunchKernelGGL(k_perm<bf16_t>, dim3(pl.nPB), dim3(kThreads), (size_t)p->E * 8, st, a);
     }
-    if (x_perm) {
-        const size_t row_bytes = (size_t)p->d * elem_size(p->dtype);
-        int grid = (pl.N + 3) / 4;  // one wavefront per row while rows last
-        if (grid > 8192) grid = 8192;
-        hipLaunchKernelGGL(k_gather, dim3(grid), dim3(kThreads), 0, st, a, row_bytes);
-    }
+    if (x_perm) hipLaunchKernelGGL(k_gather, dim3(ggrid), dim3(kThreads), 0, st, a, row_bytes);
     hipLaunchKernelGGL(k_dispatch_finish, dim3(16), dim3(kThreads), 0, st, a);
     return hip_ok(hipGetLastError());
 }

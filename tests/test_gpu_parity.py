@@ -263,6 +263,40 @@ def test_dispatch_empty_experts():
     assert np.array_equal(buf.perm.cpu().numpy(), perm)
 
 
+def test_dispatch_many_blocks_and_experts():
+    """Indices only, at a size whose block histograms (T/64 x E) do not fit the short form's LDS: the
+    form with the single-workgroup plan runs.  Random distinct experts per token, seeded."""
+    B = _binding()
+    T, d, E, k = 8192, 64, 256, 4
+    p = B.problem(T, d, E, k, 64, 8, "bf16")
+    buf = B.Buffers(p)
+    g = torch.Generator().manual_seed(77)
+    ridx = torch.rand((T, E), generator=g).argsort(dim=1)[:, :k].to(torch.int32).contiguous()
+    for rep in range(2):
+        B.moe_dispatch(p, None, ridx.cuda(), buf.counts, buf.offsets, buf.perm, buf.inv_perm, None, buf.workspace)
+        torch.cuda.synchronize()
+        counts, offsets, perm, inv = oracle.dispatch(ridx.numpy(), E)
+        assert np.array_equal(buf.counts.cpu().numpy(), counts)
+        assert np.array_equal(buf.offsets.cpu().numpy(), offsets)
+        assert np.array_equal(buf.perm.cpu().numpy(), perm)
+        assert np.array_equal(buf.inv_perm.cpu().numpy(), inv)
+
+
+def test_dispatch_then_megakernel_share_a_workspace():
+    """A standalone dispatch between two passes of the megakernel on the same buffers leaves the
+    workspace as the megakernel needs it."""
+    B = _binding()
+    inp = W.make_inputs("mini_skew")
+    p, buf = run_forward(B, inp, 1, 0, epoch=1)
+    ref = check_against_oracle(B, inp, p, buf, 1)
+    idx = buf.topk_idx.clone()
+    B.moe_dispatch(p, inp["x"].cuda(), idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, None, buf.workspace)
+    torch.cuda.synchronize()
+    assert np.array_equal(buf.perm.cpu().numpy(), ref["perm"])
+    p, buf = run_forward(B, inp, 0, 0, epoch=2, buf=buf)
+    check_against_oracle(B, inp, p, buf, 0, ref)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_combine_identity_experts_return_x(dtype):
     """Every chosen expert returns the token itself => out = x (combine alone)."""
