@@ -64,6 +64,7 @@ struct KArgs {
     int dtype, tile_m, tile_n, signal_mode, fence_scope;
     int group_size;  // flags per fence group of the per-destination mode, 0 = all flags of a destination
     int scheduler;   // moe_scheduler_t
+    int gate_split;  // gate tasks per block of 16 tokens: each takes a slice of the reduction (1 = the whole)
     u32 epoch;
     int N, per_dest, ncb;  // slots, tokens per destination, column blocks per row
     int nPB, nRT, nCT;     // permutation blocks, gate tasks, combine tasks
@@ -104,6 +105,8 @@ struct KArgs {
     u32 *h_ready;              // [maxRB] GEMM1 tiles finished per row block
     void *h;                   // [N][f]
     void *WgT;                 // [E][d] transposed gate weights (bf16 problems with a gate), else NULL
+    double *gate_partial;      // [blocks][gate_split][16][E] partial logits of the split gate
+    u32 *gate_parts;           // [blocks] slices finished per block of 16 tokens
     u32 *dest_done;            // [R] flags stored so far per destination (ready-queue scheduler), else NULL
     u32 *rq_slots;             // [8][rq_cap] ready-queue entries, 0 = empty (ready-queue scheduler), else NULL
     int rq_cap;                // entries per ready queue: all GEMM2 tiles plus all combine tasks

@@ -305,6 +305,10 @@ static inline size_t align_up(size_t v, size_t al) { return (v + al - 1) / al * 
 
 static int elem_size(int dtype) { return dtype == MOE_DT_F32 ? 4 : 2; }
 
+// The gate is split over its reduction when there are at most kGateSplitBlocks blocks of 16 tokens,
+// into at most kGateSplitTasks tasks in all.
+constexpr int kGateSplitBlocks = 64, kGateSplitTasks = 256, kGateSplitMax = 16;
+
 enum TileKind { TK_F32 = 0, TK_LM = 1, TK_S = 3 };  // LM: 256-row tiles plus a 128-row tile for short tails
 
 struct Plan {
@@ -313,7 +317,8 @@ struct Plan {
     int kind;
     Tiling tl;
     // workspace byte offsets
-    size_t o_ctrl, o_blk_hist, o_seg_cnt, o_group_counter, o_h_ready, o_dest_done, zero_bytes;
+    size_t o_ctrl, o_blk_hist, o_seg_cnt, o_group_counter, o_h_ready, o_dest_done, o_gate_parts, zero_bytes;
+    size_t o_gate_partial;
     size_t o_rq_slots, init_zero_bytes;  // the ready queues empty themselves: zeroed by moe_workspace_init only
     int rq_cap;
     size_t o_blk_base, o_seg_begin, o_flag_base, o_dest_flag_begin, o_dest_group_begin, o_rb_base, o_rb_expert, o_rbs_base, o_rbs_expert, o_h, o_wgt, total;
@@ -384,6 +389,7 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     pl->o_seg_cnt = take((size_t)p->E * p->R * 4);
     pl->o_h_ready = take((size_t)pl->maxRB_layout * 4);
     pl->o_dest_done = take((size_t)p->R * 4);
+    pl->o_gate_parts = take((size_t)kGateSplitBlocks * 4);
     pl->zero_bytes = o;
     // What follows is zero between calls because its users leave it so (moe_workspace_init zeroes it
     // once).  Sizes are the largest any signal mode, group size or scheduler needs, so that the
@@ -406,6 +412,8 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     pl->o_rbs_base = take((size_t)(p->E + 1) * 4);
     pl->o_rbs_expert = take((size_t)p->E * 4);
     pl->o_h = take((size_t)pl->N * p->f * elem_size(p->dtype));
+    // partial logits of a gate split over its reduction (few tokens only): at most kGateSplitTasks tasks
+    pl->o_gate_partial = take((size_t)kGateSplitTasks * kRouteTokens * p->E * 8);
     // transposed gate weights (bf16 problems; unused when the routing is an input)
     pl->o_wgt = take(p->dtype == MOE_DT_BF16 ? (size_t)p->E * p->d * 2 : 0);
     pl->total = o;
@@ -642,6 +650,21 @@ int moe_megakernel_forward(const moe_problem_t *p, const void *x, const void *Wg
         const int ntt = wgt_tasks(p->d, p->E);
         a.t_gate = ntt;
         a.t_plan += ntt; a.t_perm += ntt; a.t_g1 += ntt; a.t_end += ntt;
+    } else if (Wg && pl.nRT <= kGateSplitBlocks) {
+        // few tokens: split every gate task over the reduction, so that the gate runs on more than
+        // a handful of workgroups
+        int S = kGateSplitTasks / pl.nRT;
+        const int nchunk = route_chunks(p->d, p->E, elem_size(p->dtype));
+        if (S > kGateSplitMax) S = kGateSplitMax;
+        if (S > nchunk) S = nchunk;
+        if (S > 1) {
+            const int extra = pl.nRT * (S - 1);
+            a.gate_split = S;
+            a.nRT = pl.nRT * S;
+            a.gate_partial = (double *)((char *)workspace + pl.o_gate_partial);
+            a.gate_parts = (u32 *)((char *)workspace + pl.o_gate_parts);
+            a.t_plan += extra; a.t_perm += extra; a.t_g1 += extra; a.t_end += extra;
+        }
     }
     hipStream_t st = (hipStream_t)stream;
     switch (pl.kind) {

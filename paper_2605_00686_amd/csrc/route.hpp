@@ -85,8 +85,9 @@ struct RouteLoad<float> {
 // buffered, one barrier per chunk.  Wavefronts of different groups own
 // different experts; the PARTS wavefronts of a group add their partial sums
 // into LDS one after the other (fixed order: deterministic).
+// Only the chunks [c_begin, c_end) of the reduction are summed; the bias is added if add_bias.
 template <typename ET, int NBW, int PARTS>
-__device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem) {
+__device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem, int c_begin, int c_end, bool add_bias) {
     typedef RouteLoad<ET> L;
     typedef typename L::x4_t x4_t;
     constexpr int ES = (int)sizeof(ET);
@@ -106,7 +107,6 @@ __device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem)
     const int row_bytes = E * ES;
     const bool wide = (row_bytes % 16) == 0;
     const int ppr = row_bytes / 16;
-    const int nchunk = (d + rs.KC - 1) / rs.KC;
 
     // this wavefront's expert columns; lanes past E read a valid column and are masked
     u32 keep[NBW];
@@ -180,14 +180,14 @@ __device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem)
         }
     };
 
-    fetch(0);
-    store(0, 0);
+    fetch(c_begin);
+    store(c_begin, 0);
     __syncthreads();
-    for (int c = 0; c < nchunk; ++c) {
-        const int buf = c & 1;
-        if (c + 1 < nchunk) fetch(c + 1);
+    for (int c = c_begin; c < c_end; ++c) {
+        const int buf = (c - c_begin) & 1;
+        if (c + 1 < c_end) fetch(c + 1);
         mul(c, buf);
-        if (c + 1 < nchunk) store(c + 1, buf ^ 1);
+        if (c + 1 < c_end) store(c + 1, buf ^ 1);
         __syncthreads();
     }
     // D layout: lane l, register v -> token 4*v + l/16, expert (block) l % 16
@@ -200,7 +200,7 @@ __device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int t = 4 * v + kq;
-                        const double prev = (p2 == 0) ? (a.bias ? (double)a.bias[e] : 0.0) : lg[t * E + e];
+                        const double prev = (p2 == 0) ? (add_bias && a.bias ? (double)a.bias[e] : 0.0) : lg[t * E + e];
                         lg[t * E + e] = prev + acc[b][v];
                     }
                 }
@@ -210,24 +210,30 @@ __device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem)
     }
 }
 
+// chunks of the reduction a gate task steps through (see RouteShape)
+__host__ __device__ inline int route_chunks(int d, int E, int elem_size) {
+    const RouteShape rs = route_shape(E, elem_size);
+    return (d + rs.KC - 1) / rs.KC;
+}
+
 template <typename ET>
-__device__ __forceinline__ void route_logits_dispatch(const KArgs &a, int t0, char *smem) {
+__device__ __forceinline__ void route_logits_dispatch(const KArgs &a, int t0, char *smem, int c0, int c1, bool bias) {
     const RouteShape rs = route_shape(a.E, (int)sizeof(ET));
     if (rs.parts == 4)
-        route_logits<ET, 1, 4>(a, t0, smem);
+        route_logits<ET, 1, 4>(a, t0, smem, c0, c1, bias);
     else if (rs.parts == 2) {
         if (rs.nbw == 1)
-            route_logits<ET, 1, 2>(a, t0, smem);
+            route_logits<ET, 1, 2>(a, t0, smem, c0, c1, bias);
         else
-            route_logits<ET, 2, 2>(a, t0, smem);
+            route_logits<ET, 2, 2>(a, t0, smem, c0, c1, bias);
     } else if (rs.nbw == 1)
-        route_logits<ET, 1, 1>(a, t0, smem);
+        route_logits<ET, 1, 1>(a, t0, smem, c0, c1, bias);
     else if (rs.nbw == 2)
-        route_logits<ET, 2, 1>(a, t0, smem);
+        route_logits<ET, 2, 1>(a, t0, smem, c0, c1, bias);
     else if (rs.nbw == 3)
-        route_logits<ET, 3, 1>(a, t0, smem);
+        route_logits<ET, 3, 1>(a, t0, smem, c0, c1, bias);
     else
-        route_logits<ET, 4, 1>(a, t0, smem);
+        route_logits<ET, 4, 1>(a, t0, smem, c0, c1, bias);
 }
 
 // ---- bf16 problems inside the megakernel: screen in bf16, decide in fp64 -----
@@ -658,22 +664,54 @@ __device__ __forceinline__ bool route_screened_dispatch(const KArgs &a, int t0, 
     return route_screened<4>(a, t0, smem, my_e);
 }
 
-// One gate task: tokens [task*16, task*16+16).  With a.Wg == NULL the routing
+// One gate task: tokens [b*16, b*16+16) of block b = task.  With a.Wg == NULL the routing
 // is an input and only the histograms are produced.
+// Few tokens (a decode-sized batch) mean few blocks and an idle GPU while they run, so the
+// megakernel may split the gate: a.gate_split = S > 1 tasks per block, task = b*S + s sums slice s
+// of the reduction and leaves its partial logits in the workspace; whichever task of a block
+// finishes last adds the S partial sums in slice order (so the result does not depend on who that
+// is) and goes on to the selection; the others are done.
 template <typename ET>
 __device__ __forceinline__ void route_task(const KArgs &a, int task, char *smem, bool do_hist) {
     constexpr int TPW = kRouteTokens / 4;
-    const int t0 = task * kRouteTokens;
     const int E = a.E, k = a.k;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool compute = (a.Wg != nullptr);
+    const int S = (compute && a.gate_split > 1) ? a.gate_split : 1;
+    const int block = task / S, slice = task % S;
+    const int t0 = block * kRouteTokens;
     int my_e[TPW];
 #pragma unroll
     for (int i = 0; i < TPW; ++i) my_e[i] = -1;
     MOE_TT_BEGIN();
     if (compute) {
-        if (!route_screened_dispatch<ET>(a, t0, smem, my_e)) {
-            route_logits_dispatch<ET>(a, t0, smem);
+        if (S > 1 || !route_screened_dispatch<ET>(a, t0, smem, my_e)) {
+            __shared__ int s_gate_last;
+            const int nchunk = route_chunks(a.d, E, (int)sizeof(ET));
+            route_logits_dispatch<ET>(a, t0, smem, (int)((long long)nchunk * slice / S),
+                                      (int)((long long)nchunk * (slice + 1) / S), S == 1);
+            if (S > 1) {
+                double *lg = (double *)smem;
+                const size_t per = (size_t)kRouteTokens * E;
+                double *mine = a.gate_partial + ((size_t)block * S + slice) * per;
+                for (int i = threadIdx.x; i < (int)per; i += kThreads) mine[i] = lg[i];
+                sync_stores();
+                if (threadIdx.x == 0) {
+                    fence_release(0);
+                    const u32 before = atomicAdd(&a.gate_parts[block], 1u);
+                    s_gate_last = (before == (u32)(S - 1)) ? 1 : 0;
+                    if (s_gate_last) fence_acquire(0);
+                }
+                __syncthreads();
+                if (!s_gate_last) return;
+                const double *all = a.gate_partial + (size_t)block * S * per;
+                for (int i = threadIdx.x; i < (int)per; i += kThreads) {
+                    double v = a.bias ? (double)a.bias[i % E] : 0.0;
+                    for (int s2 = 0; s2 < S; ++s2) v += all[(size_t)s2 * per + i];
+                    lg[i] = v;
+                }
+                __syncthreads();
+            }
             MOE_TT(a.ctrl, 32);
             select_full(a, t0, (const double *)smem, my_e);
         }

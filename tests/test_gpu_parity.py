@@ -162,7 +162,11 @@ def test_megakernel_gate_many_experts_and_ties(E):
     dict(T=512, d=256, E=2, k=2, f=128, R=1, dtype="bf16", seed=33, tile_m=32),
     # more destinations than a wavefront has lanes, tiny segments
     dict(T=256, d=128, E=16, k=2, f=64, R=128, dtype="bf16", seed=34, tile_m=32),
-], ids=["k_eq_E", "odd_f32", "one_dest", "many_dest"])
+    # three blocks of 16 tokens and a long reduction: the gate is split ten ways over the reduction
+    dict(T=48, d=4096, E=24, k=3, f=128, R=3, dtype="bf16", seed=35, tile_m=32, bias_std=0.5),
+    # the same in fp32 (two slices)
+    dict(T=40, d=1024, E=12, k=2, f=64, R=2, dtype="f32", seed=36),
+], ids=["k_eq_E", "odd_f32", "one_dest", "many_dest", "split_gate", "split_gate_f32"])
 @pytest.mark.parametrize("signal_mode", [0, 1])
 def test_megakernel_odd_shapes(cfg, signal_mode):
     B = _binding()
