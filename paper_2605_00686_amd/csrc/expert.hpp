@@ -643,8 +643,9 @@ struct Vec16<float> {
 
 // One token by one wavefront: out_row = sum_j wt[j] * rows[j], fp32 accumulation in
 // slot order, one rounding.  Each lane handles U 16-byte pieces of the row at a
-// time and loads 8/U slots of each before it accumulates them.
-template <typename ET, int U>
+// time and loads 8/U slots of each before it accumulates them.  STREAM: the rows are read with
+// non-temporal loads (for inputs larger than the last-level cache, which would only churn it).
+template <typename ET, int U, bool STREAM>
 __device__ __forceinline__ void combine_token(const char *rows, const float *wt, char *out_row, int k, int pieces,
                                               size_t rstride, int lane) {
     using V = Vec16<ET>;
@@ -662,7 +663,15 @@ __device__ __forceinline__ void combine_token(const char *rows, const float *wt,
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int c = c0 + 64 * u;
-                    if (j0 + jj < k && c < pieces) v[u][jj] = *(const uint4 *)(rows + (size_t)(j0 + jj) * rstride + (size_t)c * 16);
+                    if (j0 + jj < k && c < pieces) {
+                        const char *src = rows + (size_t)(j0 + jj) * rstride + (size_t)c * 16;
+                        if (STREAM) {
+                            const u32x4_t t4 = __builtin_nontemporal_load((const u32x4_t *)src);
+                            v[u][jj] = make_uint4(t4[0], t4[1], t4[2], t4[3]);
+                        } else {
+                            v[u][jj] = *(const uint4 *)src;
+                        }
+                    }
                 }
 #pragma unroll
             for (int jj = 0; jj < KB; ++jj) {
@@ -694,7 +703,7 @@ __device__ __forceinline__ void combine_token(const char *rows, const float *wt,
 // loads (a first pass that keeps many loads in flight, then a spin on whatever
 // was not ready) followed by one acquire fence at the requested scope.  Then
 // one wavefront per token, 16-byte pieces, up to eight rows in flight per lane.
-template <typename ET, bool WAIT>
+template <typename ET, bool WAIT, bool STREAM = false>
 __device__ __forceinline__ void combine_task(const KArgs &a, int task) {
     using V = Vec16<ET>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -744,13 +753,13 @@ __device__ __forceinline__ void combine_task(const KArgs &a, int task) {
         const float *wt = a.w + (size_t)t * k;
         // eight 16-byte loads in flight per lane whatever k is
         if (k == 1)
-            combine_token<ET, 8>(rows, wt, orow, k, pieces, rstride, lane);
+            combine_token<ET, 8, STREAM>(rows, wt, orow, k, pieces, rstride, lane);
         else if (k <= 2)
-            combine_token<ET, 4>(rows, wt, orow, k, pieces, rstride, lane);
+            combine_token<ET, 4, STREAM>(rows, wt, orow, k, pieces, rstride, lane);
         else if (k <= 4)
-            combine_token<ET, 2>(rows, wt, orow, k, pieces, rstride, lane);
+            combine_token<ET, 2, STREAM>(rows, wt, orow, k, pieces, rstride, lane);
         else
-            combine_token<ET, 1>(rows, wt, orow, k, pieces, rstride, lane);
+            combine_token<ET, 1, STREAM>(rows, wt, orow, k, pieces, rstride, lane);
     }
 }
 

@@ -62,9 +62,9 @@ __global__ __launch_bounds__(kThreads) void k_dispatch_finish(KArgs a) {
         z[i] = 0u;
 }
 
-template <typename ET>
+template <typename ET, bool STREAM>
 __global__ __launch_bounds__(kThreads) void k_combine(KArgs a) {
-    combine_task<ET, false>(a, blockIdx.x);
+    combine_task<ET, false, STREAM>(a, blockIdx.x);
 }
 
 // Front tasks of the megakernel from their counter, in this order:
@@ -690,10 +690,19 @@ int moe_combine(const moe_problem_t *p, const void *staging, const uint32_t *fla
     a.out = out;
     a.status_dev = status_dev;
     hipStream_t st = (hipStream_t)stream;
-    if (p->dtype == MOE_DT_F32)
-        hipLaunchKernelGGL(k_combine<float>, dim3(pl.nCT), dim3(kThreads), 0, st, a);
-    else
-        hipLaunchKernelGGL(k_combine<bf16_t>, dim3(pl.nCT), dim3(kThreads), 0, st, a);
+    // rows that do not fit the 256 MB last-level cache are streamed past it
+    const bool past_cache = (size_t)pl.N * p->d * elem_size(p->dtype) > ((size_t)192 << 20);
+    if (p->dtype == MOE_DT_F32) {
+        if (past_cache)
+            hipLaunchKernelGGL((k_combine<float, true>), dim3(pl.nCT), dim3(kThreads), 0, st, a);
+        else
+            hipLaunchKernelGGL((k_combine<float, false>), dim3(pl.nCT), dim3(kThreads), 0, st, a);
+    } else {
+        if (past_cache)
+            hipLaunchKernelGGL((k_combine<bf16_t, true>), dim3(pl.nCT), dim3(kThreads), 0, st, a);
+        else
+            hipLaunchKernelGGL((k_combine<bf16_t, false>), dim3(pl.nCT), dim3(kThreads), 0, st, a);
+    }
     return hip_ok(hipGetLastError());
 }
 
