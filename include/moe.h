@@ -44,7 +44,9 @@ typedef enum {
     MOE_ERR_NOT_READY = -4,   /* (device status) a flag was not at `epoch`     */
     MOE_ERR_HIP = -5,         /* a HIP runtime call failed                     */
     MOE_ERR_TIMEOUT = -6,     /* (device status) a bounded wait expired        */
-    MOE_ERR_BAD_ROUTING = -7  /* (device status) expert id outside [0, E)      */
+    MOE_ERR_BAD_ROUTING = -7, /* (device status) expert id outside [0, E)      */
+    MOE_ERR_CAPACITY = -8     /* (device status) an expert got more rows than  */
+                              /* moe_problem_t.capacity                        */
 } moe_status_t;
 
 typedef enum { MOE_DT_F32 = 0, MOE_DT_BF16 = 1 } moe_dtype_t;
@@ -94,6 +96,16 @@ typedef struct {
                               /* group: fences = sum over r of ceil(n_r / g).  Must */
                               /* be 0 for MOE_SIGNAL_PER_TILE                       */
     int32_t scheduler;        /* moe_scheduler_t (moe_megakernel_forward only)      */
+    int32_t capacity;         /* layout of the rows sorted by expert.  0: ragged    */
+                              /* (dropless: expert e owns rows offsets[e] ..        */
+                              /* offsets[e] + counts[e], back to back).  C > 0: the */
+                              /* padded layout of balanced routing (section 6.1,    */
+                              /* expert capacity EC = S*k/E): expert e owns the C   */
+                              /* rows from e*C, of which the first counts[e] are    */
+                              /* used; offsets[e] = e*C, perm has E*C entries with  */
+                              /* -1 in unused ones, x_perm has E*C rows (unused:    */
+                              /* zero).  Nothing is dropped: an expert with more    */
+                              /* than C rows is an error (MOE_ERR_CAPACITY)         */
 } moe_problem_t;
 
 /* number of 64-bit counters moe_megakernel_forward writes to `stats` */
@@ -125,7 +137,7 @@ const char *moe_status_string(int status);
 /* Zero the control part of a fresh workspace.  Call once after allocating it
  * (and again after a call reported MOE_ERR_TIMEOUT); every other entry point
  * leaves the workspace ready for the next call.  Size and layout of the workspace
- * depend on T, d, E, k, f, R, dtype, tile_m and tile_n only: signal_mode,
+ * depend on T, d, E, k, f, R, dtype, tile_m, tile_n and capacity only: signal_mode,
  * fence_scope, epoch, group_size and scheduler may change from call to call. */
 int moe_workspace_init(const moe_problem_t *p, void *workspace, void *stream);
 
@@ -148,6 +160,9 @@ int moe_route(const moe_problem_t *p, const void *x, const void *Wg, const float
  *   perm [N] out: slot at sorted position p (slots of one expert ascending);
  *   inv_perm [N] out: inverse.  x_perm [N,d] out, may be NULL:
  *   x_perm[p,:] = x[perm[p]/k,:].  workspace as above.
+ *   With p->capacity = C > 0, perm and x_perm have E*C entries / rows (see
+ *   moe_problem_t) and inv_perm[s] = e*C + rank; counts are exact whatever C is,
+ *   and when one exceeds C nothing else is written.
  */
 int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx, int32_t *counts,
                  int32_t *offsets, int32_t *perm, int32_t *inv_perm, void *x_perm,

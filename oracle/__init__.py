@@ -83,8 +83,13 @@ def route(x, Wg, k, bias=None, want_logits=False):
     return (idx, w, margin, logits) if want_logits else (idx, w, margin)
 
 
-def dispatch(idx, E):
-    """-> counts[E], offsets[E+1], perm[N], inv_perm[N] (all int32)."""
+def dispatch(idx, E, capacity=0):
+    """-> counts[E], offsets[E+1], perm, inv_perm[N] (all int32).
+    capacity == 0: the ragged (dropless) order, perm[N].  capacity = C > 0: the padded layout of
+    balanced routing (paper section 6.1, expert capacity EC = S*k/E): expert e owns the C sorted
+    positions from e*C, its slots fill the first counts[e] of them in the same (stable) order,
+    offsets[e] = e*C, perm[E*C] holds -1 in unused positions.  Nothing is dropped: counts beyond C
+    raise."""
     flat = _c(idx, np.int32).reshape(-1)
     N = flat.size
     counts = np.empty(E, np.int32)
@@ -92,13 +97,25 @@ def dispatch(idx, E):
     perm = np.empty(N, np.int32)
     inv = np.empty(N, np.int32)
     lib().orc_dispatch(N, E, _p(flat), _p(counts), _p(offsets), _p(perm), _p(inv))
+    if capacity > 0:
+        if counts.max() > capacity:
+            raise ValueError(f"an expert has {counts.max()} rows, capacity is {capacity}")
+        padded_off = (np.arange(E + 1, dtype=np.int64) * capacity).astype(np.int32)
+        rank = inv - offsets[flat]                      # position of slot s among its expert's slots
+        inv_c = (padded_off[flat] + rank).astype(np.int32)
+        perm_c = np.full(E * capacity, -1, np.int32)
+        perm_c[inv_c] = np.arange(N, dtype=np.int32)
+        return counts, padded_off, perm_c, inv_c
     return counts, offsets, perm, inv
 
 
 def gather(x, perm, k):
+    """x_perm[p] = x[perm[p] / k]; positions with perm[p] < 0 (padded layout) are zero rows."""
     x = _c(x)
+    perm = _c(perm, np.int32)
     out = np.empty((perm.size, x.shape[1]), x.dtype)
-    lib().orc_gather(int(perm.size), k, x.shape[1], _dt(x), _p(x), _p(_c(perm, np.int32)), _p(out))
+    lib().orc_gather(int(perm.size), k, x.shape[1], _dt(x), _p(x), _p(np.maximum(perm, 0)), _p(out))
+    out[perm < 0] = 0
     return out
 
 
@@ -166,9 +183,11 @@ def publish_plan(idx, offsets, inv_perm, E, R, d, tile_m, tile_n):
                 fences_per_tile=int(fa.value), fences_per_dest=int(fb.value))
 
 
-def forward(x, Wg, W1, W3, W2, k, bias=None, idx=None, w=None, faithful=False):
+def forward(x, Wg, W1, W3, W2, k, bias=None, idx=None, w=None, faithful=False, capacity=0):
     """Whole layer through the sorted layout: route (unless idx/w are given),
-    dispatch, experts, stage, combine.  Returns a dict of every intermediate."""
+    dispatch, experts, stage, combine.  Returns a dict of every intermediate.  The layout of the
+    sorted order (ragged or padded to `capacity` rows per expert) changes where rows sit, i.e.
+    offsets / perm / inv_perm as dispatch() returns them, and nothing that is computed."""
     if idx is None:
         idx, w, margin = route(x, Wg, k, bias)
     else:
@@ -178,5 +197,7 @@ def forward(x, Wg, W1, W3, W2, k, bias=None, idx=None, w=None, faithful=False):
     y = experts_sorted(x, W1, W3, W2, offsets, perm, k, faithful)
     st = stage(y, inv)
     out = combine(st, w, faithful)
+    if capacity > 0:
+        counts, offsets, perm, inv = dispatch(idx, E, capacity)
     return dict(idx=idx, w=w, margin=margin, counts=counts, offsets=offsets, perm=perm,
                 inv_perm=inv, y=y, staging=st, out=out)

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
 
 MOE_OK = 0
 MOE_ERR_INVALID_ARG, MOE_ERR_UNSUPPORTED, MOE_ERR_WORKSPACE = -1, -2, -3
-MOE_ERR_NOT_READY, MOE_ERR_HIP, MOE_ERR_TIMEOUT, MOE_ERR_BAD_ROUTING = -4, -5, -6, -7
+MOE_ERR_NOT_READY, MOE_ERR_HIP, MOE_ERR_TIMEOUT, MOE_ERR_BAD_ROUTING, MOE_ERR_CAPACITY = -4, -5, -6, -7, -8
 MOE_DT_F32, MOE_DT_BF16 = 0, 1
 MOE_SIGNAL_PER_TILE, MOE_SIGNAL_PER_DEST = 0, 1
 MOE_SCOPE_AGENT, MOE_SCOPE_SYSTEM = 0, 1
@@ -29,7 +29,8 @@ class MoeProblem(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("T", "d", "E", "k", "f", "R", "dtype", "tile_m", "tile_n",
                                               "signal_mode", "fence_scope")] + [("epoch", ctypes.c_uint32),
                                                                                  ("group_size", ctypes.c_int32),
-                                                                                 ("scheduler", ctypes.c_int32)]
+                                                                                 ("scheduler", ctypes.c_int32),
+                                                                                 ("capacity", ctypes.c_int32)]
 
 
 class MoeError(RuntimeError):
@@ -58,12 +59,13 @@ for _n in ("moe_workspace_init", "moe_route", "moe_dispatch", "moe_megakernel_fo
 
 
 def problem(T, d, E, k, f, R, dtype, tile_m=0, tile_n=0, signal_mode=MOE_SIGNAL_PER_DEST,
-            fence_scope=MOE_SCOPE_AGENT, epoch=1, group_size=0, scheduler=0) -> MoeProblem:
+            fence_scope=MOE_SCOPE_AGENT, epoch=1, group_size=0, scheduler=0, capacity=0) -> MoeProblem:
     if isinstance(dtype, torch.dtype):
         dtype = MOE_DT_F32 if dtype == torch.float32 else MOE_DT_BF16
     elif isinstance(dtype, str):
         dtype = MOE_DT_F32 if dtype == "f32" else MOE_DT_BF16
-    return MoeProblem(T, d, E, k, f, R, dtype, tile_m, tile_n, signal_mode, fence_scope, epoch, group_size, scheduler)
+    return MoeProblem(T, d, E, k, f, R, dtype, tile_m, tile_n, signal_mode, fence_scope, epoch, group_size, scheduler,
+                      capacity)
 
 
 def _ptr(t):
@@ -135,7 +137,7 @@ class Buffers:
         self.topk_w = torch.empty((p.T, p.k), dtype=torch.float32, device=device)
         self.counts = torch.empty(p.E, **i32)
         self.offsets = torch.empty(p.E + 1, **i32)
-        self.perm = torch.empty(N, **i32)
+        self.perm = torch.empty(p.E * p.capacity if p.capacity > 0 else N, **i32)  # sorted rows, padded or ragged
         self.inv_perm = torch.empty(N, **i32)
         self.slot_flag = torch.empty(N, **i32)
         self.staging = torch.empty((N, p.d), dtype=dt, device=device)

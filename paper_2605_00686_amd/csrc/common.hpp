@@ -65,6 +65,8 @@ struct KArgs {
     int group_size;  // flags per fence group of the per-destination mode, 0 = all flags of a destination
     int scheduler;   // moe_scheduler_t
     int gate_split;  // gate tasks per block of 16 tokens: each takes a slice of the reduction (1 = the whole)
+    int capacity;    // rows every expert owns in the sorted order, 0 = ragged layout (see moe_problem_t)
+    int NP;          // rows of the sorted order: N (ragged) or E * capacity
     u32 epoch;
     int N, per_dest, ncb;  // slots, tokens per destination, column blocks per row
     int nPB, nRT, nCT;     // permutation blocks, gate tasks, combine tasks

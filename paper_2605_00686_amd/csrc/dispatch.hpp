@@ -128,7 +128,14 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
     }
     __syncthreads();
     if (wave == 0) {
-        const int rows = wave_exclusive_scan(s_cnt, s_off, E, 1, 0);
+        int rows = wave_exclusive_scan(s_cnt, s_off, E, 1, 0);
+        if (a.capacity > 0) {  // padded layout: expert e owns the `capacity` rows from e * capacity
+            for (int e = lane; e < E; e += 64) {
+                s_off[e] = e * a.capacity;
+                if (s_cnt[e] > a.capacity) set_error(a.ctrl, MOE_ERR_CAPACITY);
+            }
+            rows = E * a.capacity;
+        }
         const int rb = wave_exclusive_scan(s_rb, s_rb, E, 1, 0);
         const int rbs = wave_exclusive_scan(s_rbs, s_rbs, E, 1, 0);
         if (lane == 0) {
@@ -242,15 +249,23 @@ __device__ __forceinline__ void block_masks(const KArgs &a, int b, u64 *mask) {
     __syncthreads();
 }
 
-// base[e]: sorted position of the block's first slot of expert e (E entries, LDS or global)
+// base[e]: sorted position of the block's first slot of expert e; counts[e]: rows of expert e (E entries
+// each, LDS or global; counts is read in the padded layout only)
 template <typename ET>
-__device__ __forceinline__ void perm_task(const KArgs &a, int b, char *smem, const int32_t *base) {
+__device__ __forceinline__ void perm_task(const KArgs &a, int b, char *smem, const int32_t *base,
+                                          const int32_t *counts) {
     const int tid = threadIdx.x;
     const int E = a.E, k = a.k;
     u64 *mask = (u64 *)smem;  // [E]
     const int t0 = b * kPermBlock;
     const int nt = min(kPermBlock, a.T - t0);
     block_masks(a, b, mask);
+    if (a.capacity > 0) {
+        // padded layout: the unused entries of perm, experts dealt round-robin to the blocks (counts[] is
+        // final: the plan, or the caller's own sums, came first)
+        for (int e = b; e < E; e += a.nPB)
+            for (int j = counts[e] + tid; j < a.capacity; j += kThreads) a.perm[(size_t)e * a.capacity + j] = -1;
+    }
     for (int q = tid; q < nt * k; q += kThreads) {
         const int s = t0 * k + q;
         const int tl = q / k;
@@ -320,6 +335,16 @@ __device__ __forceinline__ void block_perm_task(const KArgs &a, int b, const int
         if (lane == 0) off[E] = total;
     }
     __syncthreads();
+    __shared__ int s_over;
+    if (tid == 0) s_over = 0;
+    __syncthreads();
+    if (a.capacity > 0) {  // padded layout: expert e owns the `capacity` rows from e * capacity
+        for (int e = tid; e <= E; e += kThreads) {
+            off[e] = e * a.capacity;
+            if (e < E && tot[e] > a.capacity) s_over = 1;
+        }
+        __syncthreads();
+    }
     for (int e = tid; e < E; e += kThreads) base[e] += off[e];
     if (b == 0)
         for (int e = tid; e <= E; e += kThreads) {
@@ -327,7 +352,8 @@ __device__ __forceinline__ void block_perm_task(const KArgs &a, int b, const int
             if (e < E) a.counts[e] = tot[e];
         }
     __syncthreads();
-    perm_task<ET>(a, b, mask_smem, base);
+    if (s_over) return;  // an expert has more rows than the capacity: counts say so, nothing else is written
+    perm_task<ET>(a, b, mask_smem, base, tot);
 }
 
 // x_perm[p,:] = x[perm[p]/k,:] for sorted rows p = first, first+stride, ...: one
@@ -336,10 +362,14 @@ __device__ __forceinline__ void block_perm_task(const KArgs &a, int b, const int
 __device__ void gather_rows(const KArgs &a, int first, int stride, size_t row_bytes) {
     const int lane = threadIdx.x & 63;
     const int pieces = (int)(row_bytes / 16);
-    for (int p = first; p < a.N; p += stride) {
+    for (int p = first; p < a.NP; p += stride) {
         const int s = a.perm[p];
-        const uint4 *src = (const uint4 *)((const char *)a.x + (size_t)(s / a.k) * row_bytes);
         uint4 *dst = (uint4 *)((char *)a.x_perm + (size_t)p * row_bytes);
+        if (s < 0) {  // unused row of the padded layout
+            for (int c = lane; c < pieces; c += 64) dst[c] = make_uint4(0u, 0u, 0u, 0u);
+            continue;
+        }
+        const uint4 *src = (const uint4 *)((const char *)a.x + (size_t)(s / a.k) * row_bytes);
         int c = lane;
         for (; c + 192 < pieces; c += 256) {
             uint4 v0 = src[c], v1 = src[c + 64], v2 = src[c + 128], v3 = src[c + 192];

@@ -62,7 +62,7 @@ struct TileInfo {
 // tail, instead of padding the tail to 256 rows or cutting everything to 128.
 // The two kinds have separate block numbers, tables and tile code (SMALL).
 struct Tables {
-    const int32_t *offsets, *rb_base, *rb_expert, *rbs_base, *rbs_expert;
+    const int32_t *offsets, *counts, *rb_base, *rb_expert, *rbs_base, *rbs_expert;
     int n_rb, n_rbs;
 };
 
@@ -118,7 +118,7 @@ __device__ __forceinline__ TileInfo decode_tile(const KArgs &a, const Tables &tb
     // the small block follows the expert's big blocks
     ti.lrow0 = SMALL ? (tb.rb_base[e + 1] - tb.rb_base[e]) * a.tl.BM : (rb - e_rb0) * BMK;
     ti.row0 = tb.offsets[e] + ti.lrow0;
-    ti.nrows = min(BMK, tb.offsets[e + 1] - ti.row0);
+    ti.nrows = min(BMK, tb.counts[e] - ti.lrow0);  // (an expert's rows end at counts[e], not at the next expert's first row)
     ti.n0 = ct * BN;
     ti.ncols = min(BN, total_cols - ti.n0);
     ti.valid = true;
@@ -137,7 +137,7 @@ __device__ __forceinline__ TileInfo decode_block_tile(const KArgs &a, const Tabl
     ti.rb = SMALL ? tb.n_rb + rb : rb;
     ti.lrow0 = SMALL ? (tb.rb_base[e + 1] - tb.rb_base[e]) * a.tl.BM : (rb - tb.rb_base[e]) * BMK;
     ti.row0 = tb.offsets[e] + ti.lrow0;
-    ti.nrows = min(BMK, tb.offsets[e + 1] - ti.row0);
+    ti.nrows = min(BMK, tb.counts[e] - ti.lrow0);  // (an expert's rows end at counts[e], not at the next expert's first row)
     ti.n0 = ct * BN;
     ti.ncols = min(BN, total_cols - ti.n0);
     ti.valid = true;
@@ -238,10 +238,12 @@ __device__ __forceinline__ Tables decode_tables(const KArgs &a, char *smem, int 
         tb.offsets = (const int32_t *)(smem + a.tab_lds_off);
         tb.rb_base = tb.offsets + a.E + 1;
         tb.rbs_base = tb.rb_base + a.E + 1;
-        tb.rb_expert = tb.rbs_base + a.E + 1;
+        tb.counts = tb.rbs_base + a.E + 1;
+        tb.rb_expert = tb.counts + a.E + 1;
         tb.rbs_expert = tb.rb_expert + n_rb;
     } else {
         tb.offsets = a.offsets;
+        tb.counts = a.counts;
         tb.rb_base = a.rb_base;
         tb.rb_expert = a.rb_expert;
         tb.rbs_base = a.rbs_base;

@@ -33,7 +33,7 @@ __global__ __launch_bounds__(kThreads) void k_plan(KArgs a) {
 template <typename ET>
 __global__ __launch_bounds__(kThreads) void k_perm(KArgs a) {
     extern __shared__ __align__(16) char smem[];
-    if (a.ctrl->error == 0) perm_task<ET>(a, blockIdx.x, smem, a.blk_base + (size_t)blockIdx.x * a.E);
+    if (a.ctrl->error == 0) perm_task<ET>(a, blockIdx.x, smem, a.blk_base + (size_t)blockIdx.x * a.E, a.counts);
 }
 
 // standalone dispatch, short form (see block_hist_task): histograms go to blk_base, which nothing
@@ -50,6 +50,11 @@ __global__ __launch_bounds__(kThreads) void k_block_perm(KArgs a) {
 
 __global__ __launch_bounds__(kThreads) void k_gather(KArgs a, size_t row_bytes) {
     if (a.ctrl->error != 0) return;
+    if (a.capacity > 0) {  // padded layout: an expert over its capacity means perm was not written
+        int over = 0;
+        for (int e = threadIdx.x; e < a.E; e += kThreads) over |= a.counts[e] > a.capacity;
+        if (__syncthreads_or(over)) return;
+    }
     const int wave = (blockIdx.x * kThreads + threadIdx.x) >> 6;
     gather_rows(a, wave, (gridDim.x * kThreads) >> 6, row_bytes);
 }
@@ -134,7 +139,7 @@ __device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
                 seen_plan = true;
                 bad = bad || !sl->ok;
             }
-            if (!bad) perm_task<ET>(a, task - a.t_perm, smem, a.blk_base + (size_t)(task - a.t_perm) * a.E);
+            if (!bad) perm_task<ET>(a, task - a.t_perm, smem, a.blk_base + (size_t)(task - a.t_perm) * a.E, a.counts);
             sync_stores();
             if (tid == 0) {
                 fence_release(0);
@@ -196,16 +201,18 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
     if (!bad) {
         n_rb = (int)c->n_rb;
         n_rbs = (int)c->n_rbs;
-        if (a.tab_lds_off > 0) {  // [offsets | rb_base | rbs_base | rb_expert | rbs_expert]
+        if (a.tab_lds_off > 0) {  // [offsets | rb_base | rbs_base | counts | rb_expert | rbs_expert]
             int32_t *t_off = (int32_t *)(smem + a.tab_lds_off);
             int32_t *t_rbb = t_off + a.E + 1;
             int32_t *t_rsb = t_rbb + a.E + 1;
-            int32_t *t_rbe = t_rsb + a.E + 1;
+            int32_t *t_cnt = t_rsb + a.E + 1;
+            int32_t *t_rbe = t_cnt + a.E + 1;
             int32_t *t_rse = t_rbe + n_rb;
             for (int i = tid; i <= a.E; i += kThreads) {
                 t_off[i] = a.offsets[i];
                 t_rbb[i] = a.rb_base[i];
                 t_rsb[i] = a.rbs_base[i];
+                t_cnt[i] = i < a.E ? a.counts[i] : 0;
             }
             for (int i = tid; i < n_rb; i += kThreads) t_rbe[i] = a.rb_expert[i];
             for (int i = tid; i < n_rbs; i += kThreads) t_rse[i] = a.rbs_expert[i];
@@ -313,7 +320,7 @@ enum TileKind { TK_F32 = 0, TK_LM = 1, TK_S = 3 };  // LM: 256-row tiles plus a 
 
 struct Plan {
     moe_problem_t p;
-    int tile_m, tile_n, N, per_dest, ncb, nPB, nRT, nCT, comb_tokens, maxRB_layout;
+    int tile_m, tile_n, N, NP, per_dest, ncb, nPB, nRT, nCT, comb_tokens, maxRB_layout;
     int kind;
     Tiling tl;
     // workspace byte offsets
@@ -334,6 +341,8 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     if (p->tile_m < 0 || p->tile_n < 0) return MOE_ERR_INVALID_ARG;
     if (p->group_size < 0 || (p->group_size != 0 && p->signal_mode != MOE_SIGNAL_PER_DEST)) return MOE_ERR_INVALID_ARG;
     if (p->scheduler != MOE_SCHED_STATIC && p->scheduler != MOE_SCHED_READY_QUEUE) return MOE_ERR_INVALID_ARG;
+    if (p->capacity < 0) return MOE_ERR_INVALID_ARG;
+    if ((long long)p->E * p->capacity > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
     if (p->E > kMaxExperts || p->k > 32 || p->R > kMaxDest) return MOE_ERR_UNSUPPORTED;
     if ((long long)p->T * p->k > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
     const int tm = p->tile_m ? p->tile_m : 128, tn = p->tile_n ? p->tile_n : 64;
@@ -346,6 +355,7 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     pl->tile_m = tm;
     pl->tile_n = tn;
     pl->N = p->T * p->k;
+    pl->NP = p->capacity > 0 ? p->E * p->capacity : pl->N;  // rows of the sorted order (h, x_perm, perm)
     pl->per_dest = p->T / p->R;
     pl->ncb = (p->d + tn - 1) / tn;
     pl->nPB = (p->T + kPermBlock - 1) / kPermBlock;
@@ -411,7 +421,7 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     pl->o_rb_expert = take((size_t)pl->maxRB_layout * 4);
     pl->o_rbs_base = take((size_t)(p->E + 1) * 4);
     pl->o_rbs_expert = take((size_t)p->E * 4);
-    pl->o_h = take((size_t)pl->N * p->f * elem_size(p->dtype));
+    pl->o_h = take((size_t)pl->NP * p->f * elem_size(p->dtype));
     // partial logits of a gate split over its reduction (few tokens only): at most kGateSplitTasks tasks
     pl->o_gate_partial = take((size_t)kGateSplitTasks * kRouteTokens * p->E * 8);
     // transposed gate weights (bf16 problems; unused when the routing is an input)
@@ -428,7 +438,7 @@ static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
     a->signal_mode = p.signal_mode; a->fence_scope = p.fence_scope; a->epoch = p.epoch;
     a->group_size = p.group_size;
     a->scheduler = p.scheduler;
-    a->N = pl.N; a->per_dest = pl.per_dest; a->ncb = pl.ncb;
+    a->N = pl.N; a->NP = pl.NP; a->capacity = p.capacity; a->per_dest = pl.per_dest; a->ncb = pl.ncb;
     a->nPB = pl.nPB; a->nRT = pl.nRT; a->nCT = pl.nCT; a->comb_tokens = pl.comb_tokens;
     a->seg_from_blocks = (pl.per_dest % kPermBlock == 0) ? 1 : 0;
     a->tl = pl.tl;
@@ -490,7 +500,7 @@ static int launch_mega(const Plan &pl, const KArgs &a_in, hipStream_t st) {
     if (plan_smem(pl) > smem) smem = plan_smem(pl);
     // decode tables live behind everything else, for the life of the workgroup
     KArgs a = a_in;
-    const size_t tab_bytes = (size_t)(3 * (pl.p.E + 1) + pl.tl.maxRB + pl.p.E) * 4;
+    const size_t tab_bytes = (size_t)(4 * (pl.p.E + 1) + pl.tl.maxRB + pl.p.E) * 4;
     a.tab_lds_off = 0;
     if (tab_bytes <= 6 * 1024) {  // small enough that two workgroups of the 128-row tile still share a CU
         a.tab_lds_off = (int)align_up(smem, 16);
@@ -529,6 +539,7 @@ const char *moe_status_string(int s) {
         case MOE_ERR_HIP: return "HIP runtime error";
         case MOE_ERR_TIMEOUT: return "a bounded in-kernel wait expired";
         case MOE_ERR_BAD_ROUTING: return "expert id outside [0, E)";
+        case MOE_ERR_CAPACITY: return "an expert received more rows than the capacity";
         default: return "unknown status";
     }
 }
@@ -590,7 +601,7 @@ int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx,
     a.counts = counts; a.offsets = offsets; a.perm = perm; a.inv_perm = inv_perm; a.x_perm = x_perm;
     hipStream_t st = (hipStream_t)stream;
     const size_t row_bytes = (size_t)p->d * elem_size(p->dtype);
-    int ggrid = (pl.N + 3) / 4;  // gather: one wavefront per row while rows last
+    int ggrid = (pl.NP + 3) / 4;  // gather: one wavefront per row while rows last
     if (ggrid > 8192) ggrid = 8192;
     const size_t bsmem = block_perm_smem_bytes(p->E, pl.nPB);
     if (bsmem <= 64 * 1024) {

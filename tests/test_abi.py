@@ -51,17 +51,20 @@ def test_workspace_and_flag_sizes(B):
     # one workspace serves every signaling mode, fence granularity and scheduler of a problem shape
     for kw in (dict(signal_mode=0), dict(group_size=1), dict(group_size=64), dict(scheduler=1), dict(fence_scope=1)):
         assert B.moe_workspace_bytes(B.problem(4096, 2048, 128, 8, 768, 8, "bf16", **kw)) == ws, kw
+    # the padded layout holds E * capacity rows of h instead of N
+    wc = B.moe_workspace_bytes(B.problem(4096, 2048, 128, 8, 768, 8, "bf16", capacity=512))
+    assert wc - ws == (128 * 512 - 4096 * 8) * 768 * 2
 
 
 @pytest.mark.parametrize("kw", [dict(k=9, E=8), dict(T=100, R=8), dict(T=0), dict(dtype=5), dict(signal_mode=3),
                                 dict(fence_scope=2), dict(tile_m=-1), dict(group_size=-1, signal_mode=1),
-                                dict(group_size=4, signal_mode=0), dict(scheduler=2), dict(scheduler=-1)])
+                                dict(group_size=4, signal_mode=0), dict(scheduler=2), dict(scheduler=-1), dict(capacity=-1)])
 def test_invalid_problems_are_rejected_on_the_host(B, kw):
     base = dict(T=256, d=512, E=8, k=2, f=1024, R=2, dtype=1)
     base.update(kw)
     p = B.MoeProblem(base["T"], base["d"], base["E"], base["k"], base["f"], base["R"], base["dtype"],
                      base.get("tile_m", 0), 0, base.get("signal_mode", 0), base.get("fence_scope", 0), 1,
-                     base.get("group_size", 0), base.get("scheduler", 0))
+                     base.get("group_size", 0), base.get("scheduler", 0), base.get("capacity", 0))
     assert B.moe_workspace_bytes(p) == 0 and B.moe_num_flags(p) == 0
     lib = ctypes.CDLL(LIB)
     rc = lib.moe_route(ctypes.byref(p), None, None, None, None, None, None)

@@ -21,15 +21,15 @@ def _dev(inp, names):
     return {n: (inp[n].cuda() if inp.get(n) is not None else None) for n in names}
 
 
-def _problem(B, cfg, signal_mode=1, fence_scope=0, epoch=1, group_size=0, scheduler=0):
+def _problem(B, cfg, signal_mode=1, fence_scope=0, epoch=1, group_size=0, scheduler=0, capacity=0):
     return B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
                      tile_n=cfg["tile_n"], signal_mode=signal_mode, fence_scope=fence_scope, epoch=epoch,
-                     group_size=group_size, scheduler=scheduler)
+                     group_size=group_size, scheduler=scheduler, capacity=capacity)
 
 
-def run_forward(B, inp, signal_mode, fence_scope, epoch=1, buf=None, group_size=0, scheduler=0):
+def run_forward(B, inp, signal_mode, fence_scope, epoch=1, buf=None, group_size=0, scheduler=0, capacity=0):
     cfg = inp["cfg"]
-    p = _problem(B, cfg, signal_mode, fence_scope, epoch, group_size, scheduler)
+    p = _problem(B, cfg, signal_mode, fence_scope, epoch, group_size, scheduler, capacity)
     buf = buf or B.Buffers(p)
     d = _dev(inp, ("x", "Wg", "gate_bias", "W1", "W3", "W2"))
     if cfg["prerouted"] is not None:
@@ -47,7 +47,7 @@ def check_against_oracle(B, inp, p, buf, signal_mode, ref=None):
     o = parity.oracle_arrays(inp)
     idx, w, margin = parity.oracle_routing(inp)
     if ref is None:
-        ref = oracle.forward(o["x"], o["Wg"], o["W1"], o["W3"], o["W2"], cfg["k"], idx=idx, w=w)
+        ref = oracle.forward(o["x"], o["Wg"], o["W1"], o["W3"], o["W2"], cfg["k"], idx=idx, w=w, capacity=p.capacity)
     stats = buf.stats.cpu().numpy()
     assert stats[7] == 0, f"device status {stats[7]} ({B.status_string(int(stats[7]))}), timeouts {stats[6]}"
     # integer work: bit-exact
@@ -274,6 +274,69 @@ def test_dispatch_empty_experts():
     assert np.array_equal(buf.perm.cpu().numpy(), perm)
 
 
+@pytest.mark.parametrize("name", ["mini_bf16", "mini_skew", "mini_decode", "mini_odd", "mini_f32"])
+def test_megakernel_padded_layout(name):
+    """The padded layout of balanced routing (section 6.1: every expert owns `capacity` rows of the sorted
+    order): same outputs, offsets = e * capacity, perm with -1 in unused rows.  Capacity = the largest
+    expert's rows (nothing spare) and something larger; both signaling modes; then a capacity that is too
+    small: reported, and the workspace still good for the next call."""
+    B = _binding()
+    inp = W.make_inputs(name)
+    idx, _, _ = parity.oracle_routing(inp)
+    cmax = int(np.bincount(idx.reshape(-1), minlength=inp["cfg"]["E"]).max())
+    for mode, cap in [(1, cmax), (0, cmax + 37)]:
+        print(f"case {name} padded layout, capacity {cap}, signal_mode {mode}", flush=True)
+        p, buf = run_forward(B, inp, mode, 0, capacity=cap)
+        check_against_oracle(B, inp, p, buf, mode)
+    print(f"case {name} capacity {cmax - 1}: too small", flush=True)
+    p, buf = run_forward(B, inp, 1, 0, capacity=cmax - 1)
+    assert int(buf.stats.cpu().numpy()[7]) == B.MOE_ERR_CAPACITY
+    assert np.array_equal(buf.counts.cpu().numpy(), np.bincount(idx.reshape(-1), minlength=inp["cfg"]["E"]))
+    # the same buffers again, with routing given that fits: the failed call left the workspace usable
+    T, k, E = inp["cfg"]["T"], inp["cfg"]["k"], inp["cfg"]["E"]
+    if T * k % E == 0 and T * k // E <= cmax - 1:
+        inp2 = dict(inp)
+        inp2["cfg"] = dict(inp["cfg"], prerouted=dict(kind="given"))
+        inp2["Wg"], inp2["gate_bias"] = None, None
+        inp2["topk_idx"] = ((torch.arange(T)[:, None] * k + torch.arange(k)[None, :]) % E).to(torch.int32)
+        inp2["topk_w"] = torch.full((T, k), 1.0 / k)
+        p, buf = run_forward(B, inp2, 1, 0, epoch=2, buf=buf, capacity=cmax - 1)
+        check_against_oracle(B, inp2, p, buf, 1)
+
+
+@pytest.mark.parametrize("name", ["mini_bf16", "mini_decode"])
+def test_dispatch_padded_layout(name):
+    B = _binding()
+    inp = W.make_inputs(name, with_weights=False)
+    cfg = inp["cfg"]
+    ridx, _, _ = parity.oracle_routing(inp)
+    cmax = int(np.bincount(ridx.reshape(-1), minlength=cfg["E"]).max())
+    x = inp["x"].cuda()
+    idx = torch.from_numpy(ridx).cuda()
+    for cap in (cmax, cmax + 5):
+        print(f"case dispatch {name} capacity {cap}", flush=True)
+        p = _problem(B, cfg, capacity=cap)
+        buf = B.Buffers(p)
+        x_perm = torch.full((cfg["E"] * cap, cfg["d"]), float("nan"), dtype=x.dtype, device="cuda")
+        B.moe_dispatch(p, x, idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, x_perm, buf.workspace)
+        torch.cuda.synchronize()
+        counts, offsets, perm, inv = oracle.dispatch(ridx, cfg["E"], capacity=cap)
+        assert np.array_equal(buf.counts.cpu().numpy(), counts)
+        assert np.array_equal(buf.offsets.cpu().numpy(), offsets)
+        assert np.array_equal(buf.perm.cpu().numpy(), perm)
+        assert np.array_equal(buf.inv_perm.cpu().numpy(), inv)
+        assert np.array_equal(W.as_oracle_array(x_perm), oracle.gather(W.as_oracle_array(inp["x"]), perm, cfg["k"]))
+    # too small: counts are exact, nothing else is written
+    p = _problem(B, cfg, capacity=cmax - 1)
+    buf = B.Buffers(p)
+    buf.perm.fill_(-7)
+    x_perm = torch.full((cfg["E"] * (cmax - 1), cfg["d"]), 3.0, dtype=x.dtype, device="cuda")
+    B.moe_dispatch(p, x, idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, x_perm, buf.workspace)
+    torch.cuda.synchronize()
+    assert np.array_equal(buf.counts.cpu().numpy(), counts)
+    assert (buf.perm == -7).all().item() and (x_perm == 3.0).all().item()
+
+
 def test_dispatch_many_blocks_and_experts():
     """Indices only, at a size whose block histograms (T/64 x E) do not fit the short form's LDS: the
     form with the single-workgroup plan runs.  Random distinct experts per token, seeded."""
@@ -291,6 +354,16 @@ def test_dispatch_many_blocks_and_experts():
         assert np.array_equal(buf.offsets.cpu().numpy(), offsets)
         assert np.array_equal(buf.perm.cpu().numpy(), perm)
         assert np.array_equal(buf.inv_perm.cpu().numpy(), inv)
+    # the padded layout through the same form
+    cap = int(counts.max()) + 1
+    p = B.problem(T, d, E, k, 64, 8, "bf16", capacity=cap)
+    buf = B.Buffers(p)
+    B.moe_dispatch(p, None, ridx.cuda(), buf.counts, buf.offsets, buf.perm, buf.inv_perm, None, buf.workspace)
+    torch.cuda.synchronize()
+    counts, offsets, perm, inv = oracle.dispatch(ridx.numpy(), E, capacity=cap)
+    assert np.array_equal(buf.offsets.cpu().numpy(), offsets)
+    assert np.array_equal(buf.perm.cpu().numpy(), perm)
+    assert np.array_equal(buf.inv_perm.cpu().numpy(), inv)
 
 
 def test_dispatch_then_megakernel_share_a_workspace():

@@ -141,6 +141,58 @@ def dense_swiglu(x, W1, W3, W2):
     return (g * scipy.special.expit(g) * u) @ W2
 
 
+def test_dispatch_padded_layout_balanced_routing_has_no_padding():
+    """Balanced routing (paper section 6.1): token t picks experts (t*k + j) mod E, so every expert gets
+    exactly EC = T*k/E slots; with capacity = EC the padded layout IS the ragged one."""
+    T, k, E = 48, 4, 16
+    idx = ((np.arange(T)[:, None] * k + np.arange(k)[None, :]) % E).astype(np.int32)
+    EC = T * k // E
+    ragged = oracle.dispatch(idx, E)
+    padded = oracle.dispatch(idx, E, capacity=EC)
+    assert np.all(ragged[0] == EC)
+    for a, b in zip(ragged, padded):
+        assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("T,k,E,C,seed", [(40, 2, 6, 0, 1), (100, 3, 7, 64, 2), (17, 1, 3, 0, 3)])
+def test_dispatch_padded_layout_against_enumeration(T, k, E, C, seed):
+    """Padded layout, by its definition: expert e's slots, ascending, at positions e*C ..; -1 behind them."""
+    rng = np.random.default_rng(seed)
+    idx = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    flat = idx.reshape(-1)
+    cmax = int(np.bincount(flat, minlength=E).max())
+    C = C or cmax  # (C = 0 in the parameters: the tightest capacity that drops nothing)
+    counts, offsets, perm, inv = oracle.dispatch(idx, E, capacity=C)
+    assert np.array_equal(offsets, np.arange(E + 1) * C)
+    want = np.full(E * C, -1, np.int64)
+    for e in range(E):
+        slots = [s for s in range(T * k) if flat[s] == e]
+        assert counts[e] == len(slots)
+        want[e * C:e * C + len(slots)] = slots
+    assert np.array_equal(perm, want)
+    assert np.array_equal(perm[inv], np.arange(T * k))
+    assert (perm < 0).sum() == E * C - T * k
+    # rows of unused positions are zero, the others are the token's row
+    x = rng.standard_normal((T, 5)).astype(np.float32)
+    xp = oracle.gather(x, perm, k)
+    assert np.array_equal(xp[perm >= 0], x[perm[perm >= 0] // k]) and not xp[perm < 0].any()
+    with pytest.raises(ValueError):
+        oracle.dispatch(idx, E, capacity=cmax - 1)
+
+
+def test_forward_does_not_depend_on_the_layout():
+    rng = np.random.default_rng(5)
+    T, d, E, k, f = 24, 16, 4, 2, 8
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    Wg = rng.standard_normal((d, E)).astype(np.float32)
+    W1, W3 = (0.1 * rng.standard_normal((E, d, f)).astype(np.float32) for _ in range(2))
+    W2 = 0.1 * rng.standard_normal((E, f, d)).astype(np.float32)
+    a = oracle.forward(x, Wg, W1, W3, W2, k)
+    b = oracle.forward(x, Wg, W1, W3, W2, k, capacity=int(a["counts"].max()) + 3)
+    assert np.array_equal(a["out"], b["out"]) and np.array_equal(a["staging"], b["staging"])
+    assert np.array_equal(b["perm"][b["inv_perm"]], np.arange(T * k))
+
+
 def test_experts_single_expert_is_a_dense_mlp():
     r = rng(20)
     T, d, f = 10, 24, 40
