@@ -16,13 +16,13 @@ pytestmark = pytest.mark.gpu
 SAMPLES = {"cfg1": 256, "cfg2": 48, "cfg3": 48, "cfg4": 12, "cfg5": 24, "cfg6": 24}
 
 
-def _run(name, signal_mode, fence_scope, inp=None, buf=None, epoch=1, group_size=0, scheduler=0):
+def _run(name, signal_mode, fence_scope, inp=None, buf=None, epoch=1, group_size=0, scheduler=0, capacity=0):
     from paper_2605_00686_amd import binding as B
     inp = inp or W.make_inputs(name)
     cfg = inp["cfg"]
     p = B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
                   tile_n=cfg["tile_n"], signal_mode=signal_mode, fence_scope=fence_scope, epoch=epoch,
-                  group_size=group_size, scheduler=scheduler)
+                  group_size=group_size, scheduler=scheduler, capacity=capacity)
     buf = buf or B.Buffers(p)
     dev = inp.setdefault("_dev", {n: (inp[n].cuda() if inp[n] is not None else None)
                                   for n in ("x", "Wg", "gate_bias", "W1", "W3", "W2")})
@@ -56,10 +56,13 @@ def _check(B, inp, p, buf, signal_mode, name, cache):
     mm = None if r["margin"] is None else float(r["margin"].min())
     assert np.array_equal(buf.topk_idx.cpu().numpy(), r["idx"]), f"routing differs; min margin {mm}"
     np.testing.assert_allclose(buf.topk_w.cpu().numpy(), r["w"], rtol=1e-5, atol=1e-7)
-    assert np.array_equal(buf.counts.cpu().numpy(), r["counts"])
-    assert np.array_equal(buf.offsets.cpu().numpy(), r["offsets"])
-    assert np.array_equal(buf.perm.cpu().numpy(), r["perm"])
-    assert np.array_equal(buf.inv_perm.cpu().numpy(), r["inv"])
+    counts, offsets, perm, inv = r["counts"], r["offsets"], r["perm"], r["inv"]
+    if p.capacity > 0:  # the padded layout: same rows, other positions
+        counts, offsets, perm, inv = oracle.dispatch(r["idx"], cfg["E"], capacity=p.capacity)
+    assert np.array_equal(buf.counts.cpu().numpy(), counts)
+    assert np.array_equal(buf.offsets.cpu().numpy(), offsets)
+    assert np.array_equal(buf.perm.cpu().numpy(), perm)
+    assert np.array_equal(buf.inv_perm.cpu().numpy(), inv)
     plan = r["plan"]
     assert np.array_equal(buf.slot_flag.cpu().numpy(), plan["slot_flag"])
     nfl = plan["n_flags"]
@@ -101,3 +104,7 @@ def test_fullsize_parity(name):
     assert buf.stats.cpu().numpy()[16] > 0
     B, inp, p, buf = _run(name, 1, 0, inp=inp, buf=buf, epoch=7)
     _check(B, inp, p, buf, 1, name, cache)
+    if name in ("cfg2", "cfg5"):  # the padded layout at full size (its own buffers: h and perm are larger)
+        cap = int(cache["ref"]["counts"].max()) + 8
+        B, inp, p, buf = _run(name, 1, 0, inp=inp, epoch=8, capacity=cap)
+        _check(B, inp, p, buf, 1, name, cache)
