@@ -46,6 +46,8 @@ using CfgL = TileCfg<4, 4, 2, 2, 32, 4>;  // 256 x 256, wavefront 128 x 128
 using CfgM = TileCfg<2, 4, 2, 2, 64, 3>;  // 128 x 256, wavefront  64 x 128
 using CfgS = TileCfg<1, 2, 1, 4, 64, 4>;  //  32 x 256, wavefront  32 x  64, deep pipeline: weight streaming
 
+constexpr int kTileGroupRows = 4, kTileGroupCols = 8;  // see decode_tile
+
 struct TileInfo {
     int e, rb, row0, nrows, lrow0, n0, ncols;
     bool valid;
@@ -96,8 +98,8 @@ __device__ __forceinline__ TileQueue tile_queue(const KArgs &a, int n_rb, int n_
 }
 
 // Entry i of one phase and kind of a queue -> tile.  Inside the share, the tiles
-// of one expert are consecutive and the column tile varies slowest, so tiles
-// running at the same time share one weight column block and the expert's rows.
+// of one expert are consecutive, in an order that lets tiles running at the same
+// time share weight column blocks and rows in the XCD's L2 (see below).
 // ti.rb numbers big blocks from 0 and small blocks from n_rb (index into h_ready).
 template <bool SMALL>
 __device__ __forceinline__ TileInfo decode_tile(const KArgs &a, const Tables &tb, const TileQueue &tq, int i, int NT,
@@ -111,7 +113,17 @@ __device__ __forceinline__ TileInfo decode_tile(const KArgs &a, const Tables &tb
     const int s0 = max(e_rb0, q0), s1 = min(base[e + 1], q1);  // the expert's row blocks of this kind in this share
     const int nrb = s1 - s0;
     const int loc = i - (s0 - q0) * NT;
-    const int ct = loc / nrb, rbl = loc % nrb;
+    // The expert's tiles (nrb row blocks x NT column tiles) are listed in blocks of GR row blocks x
+    // GC column tiles, column tile slowest inside a block: the 32 workgroups of an XCD then work on
+    // 4 + 8 different operand panels at a time.  (All row blocks of one column tile side by side, 16 + 2
+    // panels when an expert has 16 row blocks, made the L2 fetch 28 GB per cfg4 launch.)
+    constexpr int GR = kTileGroupRows, GC = kTileGroupCols;
+    const int rg = min(loc / (GR * NT), (nrb - 1) / GR);
+    const int l2 = loc - rg * GR * NT;
+    const int rows_g = min(GR, nrb - rg * GR);
+    const int cg = l2 / (rows_g * GC);
+    const int l3 = l2 - cg * rows_g * GC;
+    const int ct = cg * GC + l3 / rows_g, rbl = rg * GR + l3 % rows_g;
     const int rb = s0 + rbl;
     ti.e = e;
     ti.rb = SMALL ? tb.n_rb + rb : rb;
