@@ -147,6 +147,8 @@ void orc_route(int T, int d, int E, int k, int dt, const void *x, const void *Wg
 void orc_dispatch(int N, int E, const int32_t *idx, int32_t *counts, int32_t *offsets,
                   int32_t *perm, int32_t *inv_perm)
 {
+    if (E <= 0 || N < 0)
+        return;
     for (int e = 0; e < E; ++e)
         counts[e] = 0;
     for (int s = 0; s < N; ++s)
