@@ -6,7 +6,7 @@ publish with flags, combine) in one persistent-kernel launch over one batch of
 seeded synthetic input already resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
-                  [--signal-mode per_dest|per_tile] [--scope agent|system] [--group-size G] [--scheduler static|ready_queue]
+                  [--signal-mode per_dest|per_tile] [--scope agent|system] [--group-size G] [--scheduler static|ready_queue] [--capacity C]
                   [--ops] [--no-cpu]
 """
 from __future__ import annotations
@@ -72,7 +72,7 @@ def standalone_ops(B, torch, p, buf, dev, cfg, steps):
     T, d, E, k = cfg["T"], cfg["d"], cfg["E"], cfg["k"]
     sz = 4 if cfg["dtype"] == "f32" else 2
     N = T * k
-    x_perm = torch.empty((N, d), dtype=dev["x"].dtype, device="cuda")
+    x_perm = torch.empty((p.E * p.capacity if p.capacity > 0 else N, d), dtype=dev["x"].dtype, device="cuda")
     idx2, w2 = torch.empty_like(buf.topk_idx), torch.empty_like(buf.topk_w)
 
     def timed(fn):
@@ -115,6 +115,9 @@ def main():
                     help="per_dest only: flags per fence group (0 = all flags of a destination)")
     ap.add_argument("--scheduler", default="static", choices=["static", "ready_queue"],
                     help="order of expert tiles and combine tasks: dependency-ordered lists, or ready queues")
+    ap.add_argument("--capacity", type=int, default=0,
+                    help="rows per expert in the padded layout of the sorted order (0 = ragged layout; -1 = the largest "
+                         "expert's row count of this workload, rounded up to a multiple of 64)")
     ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens for the CPU baseline (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -137,15 +140,30 @@ def main():
     cfg = inp["cfg"]
     mode = B.MOE_SIGNAL_PER_DEST if args.signal_mode == "per_dest" else B.MOE_SIGNAL_PER_TILE
     scope = B.MOE_SCOPE_AGENT if args.scope == "agent" else B.MOE_SCOPE_SYSTEM
-    p = B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
-                  tile_n=cfg["tile_n"], signal_mode=mode, fence_scope=scope, epoch=1, group_size=args.group_size,
-                  scheduler=1 if args.scheduler == "ready_queue" else 0)
+    def make_problem(capacity):
+        return B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
+                         tile_n=cfg["tile_n"], signal_mode=mode, fence_scope=scope, epoch=1, group_size=args.group_size,
+                         scheduler=1 if args.scheduler == "ready_queue" else 0, capacity=capacity)
+
+    capacity = args.capacity
+    p = make_problem(max(capacity, 0))
     buf = B.Buffers(p)
     dev = {n: (inp[n].cuda() if inp[n] is not None else None) for n in ("x", "Wg", "gate_bias", "W1", "W3", "W2")}
     if cfg["prerouted"] is not None:
         buf.topk_idx.copy_(inp["topk_idx"])
         buf.topk_w.copy_(inp["topk_w"])
     torch.cuda.synchronize()
+    if capacity < 0:
+        # one untimed pass in the ragged layout tells how many rows the largest expert gets
+        B.forward(p, buf, dev["x"], dev["Wg"], dev["gate_bias"], dev["W1"], dev["W3"], dev["W2"])
+        torch.cuda.synchronize()
+        capacity = (int(buf.counts.max().item()) + 63) // 64 * 64
+        p = make_problem(capacity)
+        buf = B.Buffers(p)
+        if cfg["prerouted"] is not None:
+            buf.topk_idx.copy_(inp["topk_idx"])
+            buf.topk_w.copy_(inp["topk_w"])
+        torch.cuda.synchronize()
 
     def step():
         p.epoch += 1
@@ -187,7 +205,7 @@ def main():
         "config": {"workload": f"{args.workload}: T={cfg['T']} d={cfg['d']} E={cfg['E']} k={cfg['k']} f={cfg['f']} "
                                f"R={cfg['R']} tile={cfg['tile_m']}x{cfg['tile_n']}",
                    "signal_mode": args.signal_mode, "fence_scope": args.scope, "group_size": args.group_size,
-                   "scheduler": args.scheduler,
+                   "scheduler": args.scheduler, "capacity": capacity,
                    "launches_per_step": 1},
         "roofline": {"bound": "hbm", "kernel": "k_megakernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
