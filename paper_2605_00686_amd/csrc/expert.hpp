@@ -58,10 +58,10 @@ struct TileInfo {
 //
 // Row blocks come in one height, or in two (mixed heights): big blocks of
 // Tiling::BM rows, and for an expert whose last rows fit into Tiling::BMS rows
-// one small block for them.  Square-ish tiles move the fewest bytes per flop
-// from L2 to LDS (the 128-row tile is bound by that traffic), so an expert gets
-// as many 256-row tiles as it can fill and the 128-row tile only for a short
-// tail, instead of padding the tail to 256 rows or cutting everything to 128.
+// one small block for them.  Square-ish tiles move the fewest operand bytes per
+// flop, so an expert gets as many 256-row tiles as it can fill and the 128-row
+// tile only for a short tail, instead of padding the tail to 256 rows or cutting
+// everything to 128.
 // The two kinds have separate block numbers, tables and tile code (SMALL).
 struct Tables {
     const int32_t *offsets, *counts, *rb_base, *rb_expert, *rbs_base, *rbs_expert;
