@@ -56,6 +56,7 @@ struct Tiling {
     int NT1;    // ceil(f / BN1)
     int NT2;    // ceil(d / BN2)
     int maxRB;  // upper bound on row blocks: N / BM + E
+    int tail_with_big;  // mixed heights: only experts without a big block get a small one (see the plan)
 };
 
 // Everything a kernel needs, passed by value.

@@ -122,8 +122,12 @@ __device__ __forceinline__ void plan_task(const KArgs &a, char *smem) {
             s_rbs[e] = 0;
         } else {
             const int rem = n & (a.tl.BM - 1);
-            s_rb[e] = (n >> lbm) + (rem > a.tl.BMS ? 1 : 0);
-            s_rbs[e] = (rem > 0 && rem <= a.tl.BMS) ? 1 : 0;
+            // a short tail gets a small block; but where the layer is bound by streaming weights (tail_with_big),
+            // an expert that has big blocks keeps its tail with them, as a padded big block: its weights are then
+            // streamed once, while its tiles run side by side, and not a second time in the small-tile phase
+            const bool small = rem > 0 && rem <= a.tl.BMS && (!a.tl.tail_with_big || (n >> lbm) == 0);
+            s_rb[e] = (n >> lbm) + ((rem > 0 && !small) ? 1 : 0);
+            s_rbs[e] = small ? 1 : 0;
         }
     }
     __syncthreads();
