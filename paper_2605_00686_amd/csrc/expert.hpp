@@ -287,18 +287,10 @@ __device__ __forceinline__ u32 g1_tile(const KArgs &a, const TileInfo &ti, char 
     MOE_TT(a.ctrl, 1);
     const int ppr = ti.ncols * (int)sizeof(ET) / 16;
     char *h = (char *)a.h;
-    if ((ppr & (ppr - 1)) == 0 && ppr <= kThreads) {
-        // (the usual case: a thread keeps its piece of the row and steps through the rows; no division)
-        const int lw = 31 - __clz(ppr), c = threadIdx.x & (ppr - 1);
-        for (int r = threadIdx.x >> lw; r < ti.nrows; r += kThreads >> lw)
-            store_tile16(h + ((size_t)(ti.row0 + r) * a.f + ti.n0) * sizeof(ET) + c * 16,
-                         *(const uint4 *)(smem + r * P::C_STRIDE + c * 16));
-    } else {
-        for (int q = threadIdx.x; q < ti.nrows * ppr; q += kThreads) {
-            const int r = q / ppr, c = q % ppr;
-            store_tile16(h + ((size_t)(ti.row0 + r) * a.f + ti.n0) * sizeof(ET) + c * 16,
-                         *(const uint4 *)(smem + r * P::C_STRIDE + c * 16));
-        }
+    for (int q = threadIdx.x; q < ti.nrows * ppr; q += kThreads) {
+        const int r = q / ppr, c = q % ppr;
+        store_tile16(h + ((size_t)(ti.row0 + r) * a.f + ti.n0) * sizeof(ET) + c * 16,
+                     *(const uint4 *)(smem + r * P::C_STRIDE + c * 16));
     }
     sync_stores();
     MOE_TT(a.ctrl, 2);
@@ -379,18 +371,10 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
 
     auto copy_rows = [&](int r0, int r1, int p0, int p1) {  // 16-byte pieces [p0, p1) of rows [r0, r1)
         const int w = p1 - p0;
-        if ((w & (w - 1)) == 0 && w <= kThreads) {
-            // (the usual case: a thread keeps its piece of the row and steps through the rows; no division)
-            const int lw = 31 - __clz(w), c = p0 + (tid & (w - 1));
-            for (int r = r0 + (tid >> lw); r < r1; r += kThreads >> lw)
-                store_tile16(staging + ((size_t)s_slot[r] * a.d + ti.n0) * ES + c * 16,
-                             *(const uint4 *)(smem + r * P::C_STRIDE + c * 16));
-        } else {
-            for (int q = tid; q < (r1 - r0) * w; q += kThreads) {
-                const int r = r0 + q / w, c = p0 + q % w;
-                store_tile16(staging + ((size_t)s_slot[r] * a.d + ti.n0) * ES + c * 16,
-                             *(const uint4 *)(smem + r * P::C_STRIDE + c * 16));
-            }
+        for (int q = tid; q < (r1 - r0) * w; q += kThreads) {
+            const int r = r0 + q / w, c = p0 + q % w;
+            store_tile16(staging + ((size_t)s_slot[r] * a.d + ti.n0) * ES + c * 16,
+                         *(const uint4 *)(smem + r * P::C_STRIDE + c * 16));
         }
     };
 
