@@ -380,8 +380,8 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
         pl->tl.BN2 = 256;
     }
     pl->tl.BMS = pl->kind == TK_LM ? CfgM::BM : 0;
-    // few rows per expert: the layer streams weights (measured: -1.2 % on cfg2; +2 to 4 % on cfg3 and cfg4, which
-    // have thousands of rows per expert and are bound by the matrix cores, if it were applied there)
+    // few rows per expert: the layer streams weights (measured: about -1 % on cfg2; +2 to 4 % on cfg3 and cfg4,
+    // which have thousands of rows per expert and are bound by the matrix cores, if it were applied there)
     pl->tl.tail_with_big = avg < 512 ? 1 : 0;
     if (pl->tl.BMS % tm != 0) return MOE_ERR_UNSUPPORTED;
     if (bm % tm != 0) return MOE_ERR_UNSUPPORTED;
