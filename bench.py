@@ -26,7 +26,7 @@ MFMA_BF16_PEAK_TF = 2500.0  # dense bf16 MFMA, published
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (profiles/megakernel_cfg2_hbm_traffic.txt), keyed by workload; None = not measured.
-MEASURED_TRAFFIC_BYTES = {"cfg2": 2.063e9}
+MEASURED_TRAFFIC_BYTES = {"cfg2": 1.853e9}
 
 
 def algorithmic_bytes(cfg) -> int:
