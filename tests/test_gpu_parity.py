@@ -288,6 +288,9 @@ def test_megakernel_padded_layout(name):
         print(f"case {name} padded layout, capacity {cap}, signal_mode {mode}", flush=True)
         p, buf = run_forward(B, inp, mode, 0, capacity=cap)
         check_against_oracle(B, inp, p, buf, mode)
+    print(f"case {name} padded layout with the ready-queue scheduler and fence groups", flush=True)
+    p, buf = run_forward(B, inp, 1, 0, capacity=cmax + 1, scheduler=1, group_size=7)
+    check_against_oracle(B, inp, p, buf, 1)
     print(f"case {name} capacity {cmax - 1}: too small", flush=True)
     p, buf = run_forward(B, inp, 1, 0, capacity=cmax - 1)
     assert int(buf.stats.cpu().numpy()[7]) == B.MOE_ERR_CAPACITY
