@@ -83,7 +83,8 @@ typedef struct {
     int32_t dtype;            /* moe_dtype_t                                        */
     int32_t tile_m, tile_n;   /* publish tile rows x cols; 0 = 128 x 64 (the tile   */
                               /* of section 2.3).  tile_m in {32,64,128}, tile_n in */
-                              /* {64,128}                                           */
+                              /* {64,128}; MOE_DT_F32 takes tile_n = 64 only (else  */
+                              /* MOE_ERR_UNSUPPORTED)                               */
     int32_t signal_mode;      /* moe_signal_mode_t                                  */
     int32_t fence_scope;      /* moe_fence_scope_t                                  */
     uint32_t epoch;           /* value a flag takes when its tile is ready; nonzero */

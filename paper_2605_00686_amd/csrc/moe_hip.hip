@@ -383,6 +383,8 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     // few rows per expert: the layer streams weights (measured: about -1 % on cfg2; +2 to 4 % on cfg3 and cfg4,
     // which have thousands of rows per expert and are bound by the matrix cores, if it were applied there)
     pl->tl.tail_with_big = avg < 512 ? 1 : 0;
+    // a publish tile must lie inside one compute tile, in both directions (the fp32 tile is 64 columns wide)
+    if (pl->tl.BN2 % tn != 0) return MOE_ERR_UNSUPPORTED;
     if (pl->tl.BMS % tm != 0) return MOE_ERR_UNSUPPORTED;
     if (bm % tm != 0) return MOE_ERR_UNSUPPORTED;
     pl->tl.BM = bm;

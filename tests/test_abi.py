@@ -71,11 +71,13 @@ def test_invalid_problems_are_rejected_on_the_host(B, kw):
     assert rc == B.MOE_ERR_INVALID_ARG
 
 
-@pytest.mark.parametrize("kw", [dict(d=100), dict(tile_m=48), dict(tile_n=32), dict(E=300, k=2)])
+@pytest.mark.parametrize("kw", [dict(d=100), dict(tile_m=48), dict(tile_n=32), dict(E=300, k=2),
+                                # fp32 compute tiles are 64 columns wide: a 128-column publish tile would span two
+                                dict(dtype=0, tile_n=128)])
 def test_unsupported_problems(B, kw):
     base = dict(T=256, d=512, E=8, k=2, f=1024, R=2, tile_m=0, tile_n=0)
     base.update(kw)
-    p = B.MoeProblem(base["T"], base["d"], base["E"], base["k"], base["f"], base["R"], 1, base["tile_m"],
+    p = B.MoeProblem(base["T"], base["d"], base["E"], base["k"], base["f"], base["R"], base.get("dtype", 1), base["tile_m"],
                      base["tile_n"], 0, 0, 1)
     lib = ctypes.CDLL(LIB)
     assert lib.moe_combine(ctypes.byref(p), None, None, None, None, None, None, None) == B.MOE_ERR_UNSUPPORTED
