@@ -490,3 +490,62 @@ def test_megakernel_random_shapes():
             ref = check_against_oracle(B, inp, p, buf, mode, ref)
         ran += 1
     assert ran >= 30
+
+
+def test_standalone_entry_points_random_shapes():
+    """Thirty seeded random problems through moe_route, moe_dispatch (the oracle's routing or a skewed one
+    that leaves experts empty; ragged and padded layout; with and without the row gather; twice on one
+    workspace) and moe_combine, against the oracle."""
+    import random
+    B = _binding()
+    rng = random.Random(7)
+    for case in range(30):
+        dtype = rng.choice(["bf16", "bf16", "f32"])
+        step = 64 if dtype == "bf16" else 16
+        R = rng.choice([1, 2, 3, 4, 8, 16])
+        T = R * rng.choice([1, 2, 7, 16, 33, 64, 100, 129, 500, 1111])
+        E = rng.choice([1, 2, 3, 5, 8, 13, 16, 31, 32, 33, 64, 65, 70, 100, 128, 200, 256])
+        k = rng.randint(1, min(E, 8))
+        d = step * rng.randint(1, 8 if dtype == "bf16" else 16)
+        cfg = dict(T=T, d=d, E=E, k=k, f=64, R=R, dtype=dtype, seed=7000 + case, bias_std=rng.choice([0.0, 0.5, 2.0]))
+        print(f"case {cfg}", flush=True)
+        inp = W.make_inputs(cfg, with_weights=False)
+        p = _problem(B, inp["cfg"])
+        dv = _dev(inp, ("x", "Wg", "gate_bias"))
+        idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+        w = torch.empty((T, k), dtype=torch.float32, device="cuda")
+        B.moe_route(p, dv["x"], dv["Wg"], dv["gate_bias"], idx, w)
+        torch.cuda.synchronize()
+        ridx, rw, margin = parity.oracle_routing(inp)
+        assert np.array_equal(idx.cpu().numpy(), ridx), f"min margin {margin.min()}"
+        np.testing.assert_allclose(w.cpu().numpy(), rw, rtol=1e-5, atol=1e-7)
+        if rng.random() < 0.5 and E > k:  # a few experts take every row
+            hot = rng.sample(range(E), min(E, k + rng.randint(0, 2)))
+            sel = torch.rand((T, len(hot)), generator=torch.Generator().manual_seed(case)).argsort(dim=1)[:, :k]
+            ridx = np.ascontiguousarray(torch.tensor(hot, dtype=torch.int32)[sel].numpy())
+        cmax = int(np.bincount(ridx.reshape(-1), minlength=E).max())
+        for cap in (0, rng.choice([cmax, cmax + 3])):
+            pc = _problem(B, inp["cfg"], capacity=cap)
+            buf = B.Buffers(pc)
+            with_x = rng.random() < 0.7
+            x_perm = (torch.full((E * cap if cap else T * k, d), float("nan"), dtype=dv["x"].dtype, device="cuda")
+                      if with_x else None)
+            counts, offsets, perm, inv = oracle.dispatch(ridx, E, capacity=cap)
+            for rep in range(2):
+                B.moe_dispatch(pc, dv["x"] if with_x else None, torch.from_numpy(ridx).cuda(), buf.counts, buf.offsets,
+                               buf.perm, buf.inv_perm, x_perm, buf.workspace)
+                torch.cuda.synchronize()
+                assert np.array_equal(buf.counts.cpu().numpy(), counts)
+                assert np.array_equal(buf.offsets.cpu().numpy(), offsets)
+                assert np.array_equal(buf.perm.cpu().numpy(), perm)
+                assert np.array_equal(buf.inv_perm.cpu().numpy(), inv)
+                if with_x:
+                    assert np.array_equal(W.as_oracle_array(x_perm), oracle.gather(W.as_oracle_array(inp["x"]), perm, k))
+        staging = torch.randn((T * k, d), generator=torch.Generator().manual_seed(100 + case)).to(dv["x"].dtype)
+        out = torch.empty((T, d), dtype=dv["x"].dtype, device="cuda")
+        wt = torch.from_numpy(rw).float()
+        B.moe_combine(p, staging.cuda(), None, None, wt.cuda(), out, None)
+        torch.cuda.synchronize()
+        ref = oracle.combine(staging.float().numpy(), wt.numpy())
+        tol = 1e-6 if dtype == "f32" else 2.0 ** -8  # one rounding of the fp32 sum to the output type
+        assert np.all(np.abs(out.float().cpu().numpy() - ref) <= tol * np.maximum(np.abs(ref), 1e-3) + 1e-7)
