@@ -136,7 +136,10 @@ def main():
     from paper_2605_00686_amd import workloads as W
 
     torch.cuda.set_device(0)
-    inp = W.make_inputs(args.workload)
+    cfg = W.config(args.workload)
+    # tens of GB of weights are drawn in GPU memory (seconds instead of minutes on the host)
+    big = 3 * cfg["E"] * cfg["d"] * cfg["f"] * (4 if cfg["dtype"] == "f32" else 2) > 8e9
+    inp = W.make_inputs(args.workload, device="cuda" if big and cfg["prerouted"] is None else "cpu")
     cfg = inp["cfg"]
     mode = B.MOE_SIGNAL_PER_DEST if args.signal_mode == "per_dest" else B.MOE_SIGNAL_PER_TILE
     scope = B.MOE_SCOPE_AGENT if args.scope == "agent" else B.MOE_SCOPE_SYSTEM

@@ -32,6 +32,9 @@ CONFIGS = {
     "cfg5": dict(T=128, d=7168, E=32, k=8, f=2048, R=64, dtype="bf16", seed=5, tile_m=32),
     # third shape of Table 1 (2880, 2880, 128, 4): dimensions that are not powers of two, ragged column tiles
     "cfg6": dict(T=4096, d=2880, E=128, k=4, f=2880, R=8, dtype="bf16", seed=6),
+    # DeepSeek-V3-shaped layer with all 256 experts local (Table 1, second shape): every weight tensor has more
+    # than 2^31 elements (7.5 GB), which is what this one is for
+    "cfg7": dict(T=2048, d=7168, E=256, k=8, f=2048, R=8, dtype="bf16", seed=7, bias_std=0.5),
     # --- reduced shapes for parity tests: several tiles plus ragged tails ---
     "mini_f32": dict(T=96, d=192, E=6, k=2, f=320, R=4, dtype="f32", seed=11),
     "mini_bf16": dict(T=384, d=512, E=8, k=2, f=640, R=4, dtype="bf16", seed=12, bias_std=0.5),
@@ -60,36 +63,39 @@ def torch_dtype(cfg) -> torch.dtype:
 
 
 def _normal(gen, shape, std, dtype):
-    """N(0, std) drawn in fp32 on the CPU, then rounded once to ``dtype``.
+    """N(0, std) drawn in fp32 on the generator's device, then rounded once to ``dtype``.
     Leading-dimension chunks bound the fp32 temporary for multi-GB tensors."""
-    out = torch.empty(shape, dtype=dtype)
+    out = torch.empty(shape, dtype=dtype, device=gen.device)
     if len(shape) == 3:
         for e in range(shape[0]):
-            out[e] = (torch.randn(shape[1:], generator=gen, dtype=torch.float32) * std).to(dtype)
+            out[e] = (torch.randn(shape[1:], generator=gen, dtype=torch.float32, device=gen.device) * std).to(dtype)
     else:
-        out.copy_((torch.randn(shape, generator=gen, dtype=torch.float32) * std).to(dtype))
+        out.copy_((torch.randn(shape, generator=gen, dtype=torch.float32, device=gen.device) * std).to(dtype))
     return out
 
 
-def make_inputs(name_or_cfg, with_weights: bool = True) -> dict:
-    """CPU tensors for one workload: x[T,d], Wg[d,E], gate_bias[E] or None,
+def make_inputs(name_or_cfg, with_weights: bool = True, device: str = "cpu") -> dict:
+    """Tensors for one workload: x[T,d], Wg[d,E], gate_bias[E] or None,
     W1/W3[E,d,f], W2[E,f,d] in the config dtype; for pre-routed configs also
-    topk_idx[T,1] int32 and topk_w[T,1] fp32 (and no Wg)."""
+    topk_idx[T,1] int32 and topk_w[T,1] fp32 (and no Wg).  Drawn on the CPU by
+    default; ``device="cuda"`` draws them in GPU memory with that device's
+    seeded generator (other values than the CPU's for the same seed; tens of GB
+    of weights then take seconds instead of minutes)."""
     cfg = config(name_or_cfg)
     T, d, E, k, f = cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"]
     dt = torch_dtype(cfg)
-    gen = torch.Generator(device="cpu").manual_seed(int(cfg["seed"]))
+    gen = torch.Generator(device=device).manual_seed(int(cfg["seed"]))
     out = {"cfg": cfg}
     out["x"] = _normal(gen, (T, d), 1.0, dt)
     pre = cfg["prerouted"]
     if pre is None:
         out["Wg"] = _normal(gen, (d, E), W_STD, dt)
-        out["gate_bias"] = (torch.randn(E, generator=gen, dtype=torch.float32) * cfg["bias_std"]
+        out["gate_bias"] = (torch.randn(E, generator=gen, dtype=torch.float32, device=gen.device) * cfg["bias_std"]
                             if cfg["bias_std"] > 0 else None)
         out["topk_idx"] = None
         out["topk_w"] = None
     else:
-        assert k == 1
+        assert k == 1 and device == "cpu"
         # popularity of the local experts: global ranks 1..E of a Zipf law over all experts
         ranks = torch.arange(1, E + 1, dtype=torch.float64)
         pmf = ranks.pow(-float(pre["zipf"]))

@@ -13,7 +13,7 @@ from tests import parity
 
 pytestmark = pytest.mark.gpu
 
-SAMPLES = {"cfg1": 256, "cfg2": 48, "cfg3": 48, "cfg4": 12, "cfg5": 24, "cfg6": 24}
+SAMPLES = {"cfg1": 256, "cfg2": 48, "cfg3": 48, "cfg4": 12, "cfg5": 24, "cfg6": 24, "cfg7": 8}
 
 
 def _run(name, signal_mode, fence_scope, inp=None, buf=None, epoch=1, group_size=0, scheduler=0, capacity=0):
@@ -108,3 +108,20 @@ def test_fullsize_parity(name):
         cap = int(cache["ref"]["counts"].max()) + 8
         B, inp, p, buf = _run(name, 1, 0, inp=inp, epoch=8, capacity=cap)
         _check(B, inp, p, buf, 1, name, cache)
+
+
+def test_fullsize_weights_beyond_2g_elements():
+    """All 256 experts of the DeepSeek-V3-shaped layer on one GPU: W1, W3 and W2 have 3.76e9 elements each, so
+    element offsets pass 2^31 and byte offsets 2^32 in every operand stream.  Inputs are drawn in GPU memory
+    (22.5 GB of weights) and copied back for the oracle; checks as in the other full-size cases."""
+    name = "cfg7"
+    print(f"case full-size {name}", flush=True)
+    inp = W.make_inputs(name, device="cuda")
+    print("inputs drawn", flush=True)
+    cache = {}
+    B, inp, p, buf = _run(name, 1, 0, inp=inp)
+    _check(B, inp, p, buf, 1, name, cache)
+    hot = np.unique(cache["ref"]["idx"][cache["ref"]["tok"]])
+    assert hot.max() >= 147, "no sampled token reaches an expert whose weights start beyond 2^31 elements"
+    B, inp, p, buf = _run(name, 1, 0, inp=inp, buf=buf, epoch=2, scheduler=1)
+    _check(B, inp, p, buf, 1, name, cache)
