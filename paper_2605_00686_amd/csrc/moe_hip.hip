@@ -659,28 +659,28 @@ int moe_megakernel_forward(const moe_problem_t *p, const void *x, const void *Wg
     a.idx = topk_idx; a.w = topk_w; a.counts = counts; a.offsets = offsets; a.perm = perm; a.inv_perm = inv_perm;
     a.slot_flag = slot_flag; a.staging = staging; a.flags = flags; a.out = out;
     a.stats = (u64 *)stats;
-    if (Wg && p->dtype == MOE_DT_BF16 && p->E >= 64) {
-        // bf16 gate: screen on the bf16 matrix cores, exact fp64 logits for the candidates only; this
-        // needs the gate weights transposed, which the first front tasks of the kernel write
+    // few tokens (at most kGateSplitBlocks blocks of 16): split every gate task over the reduction, so that
+    // the gate runs on all workgroups instead of a handful
+    int S = 1;
+    if (Wg && pl.nRT <= kGateSplitBlocks) {
+        S = kGateSplitTasks / pl.nRT;
+        if (S > kGateSplitMax) S = kGateSplitMax;
+        if (S > route_max_slices(p->d)) S = route_max_slices(p->d);
+    }
+    if (S > 1) {
+        const int extra = pl.nRT * (S - 1);
+        a.gate_split = S;
+        a.nRT = pl.nRT * S;
+        a.gate_partial = (double *)((char *)workspace + pl.o_gate_partial);
+        a.gate_parts = (u32 *)((char *)workspace + pl.o_gate_parts);
+        a.t_plan += extra; a.t_perm += extra; a.t_g1 += extra; a.t_end += extra;
+    } else if (Wg && p->dtype == MOE_DT_BF16 && p->E >= 64) {
+        // bf16 gate with one task or more per workgroup: screen on the bf16 matrix cores, exact fp64 logits for
+        // the candidates only; this needs the gate weights transposed, which the first front tasks of the kernel write
         a.WgT = (char *)workspace + pl.o_wgt;
         const int ntt = wgt_tasks(p->d, p->E);
         a.t_gate = ntt;
         a.t_plan += ntt; a.t_perm += ntt; a.t_g1 += ntt; a.t_end += ntt;
-    } else if (Wg && pl.nRT <= kGateSplitBlocks) {
-        // few tokens: split every gate task over the reduction, so that the gate runs on more than
-        // a handful of workgroups
-        int S = kGateSplitTasks / pl.nRT;
-        const int nchunk = route_chunks(p->d, p->E, elem_size(p->dtype));
-        if (S > kGateSplitMax) S = kGateSplitMax;
-        if (S > nchunk) S = nchunk;
-        if (S > 1) {
-            const int extra = pl.nRT * (S - 1);
-            a.gate_split = S;
-            a.nRT = pl.nRT * S;
-            a.gate_partial = (double *)((char *)workspace + pl.o_gate_partial);
-            a.gate_parts = (u32 *)((char *)workspace + pl.o_gate_parts);
-            a.t_plan += extra; a.t_perm += extra; a.t_g1 += extra; a.t_end += extra;
-        }
     }
     hipStream_t st = (hipStream_t)stream;
     switch (pl.kind) {

@@ -85,9 +85,10 @@ struct RouteLoad<float> {
 // buffered, one barrier per chunk.  Wavefronts of different groups own
 // different experts; the PARTS wavefronts of a group add their partial sums
 // into LDS one after the other (fixed order: deterministic).
-// Only the chunks [c_begin, c_end) of the reduction are summed; the bias is added if add_bias.
+// Only the reduction indices [k_begin, k_end) are summed (both multiples of 16), in chunks of up to
+// RouteShape::KC; the bias is added if add_bias.
 template <typename ET, int NBW, int PARTS>
-__device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem, int c_begin, int c_end, bool add_bias) {
+__device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem, int k_begin, int k_end, bool add_bias) {
     typedef RouteLoad<ET> L;
     typedef typename L::x4_t x4_t;
     constexpr int ES = (int)sizeof(ET);
@@ -123,7 +124,7 @@ __device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem,
 
     u32x4_t prew[MAXPW], prex[MAXPX];
     auto fetch = [&](int c) __attribute__((always_inline)) {  // chunk c -> registers
-        const int k0 = c * rs.KC, rows = min(rs.KC, d - k0);
+        const int k0 = k_begin + c * rs.KC, rows = min(rs.KC, k_end - k0);
         if (wide) {
 #pragma unroll
             for (int i = 0; i < MAXPW; ++i) {
@@ -142,7 +143,7 @@ __device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem,
         }
     };
     auto store = [&](int c, int buf) __attribute__((always_inline)) {  // registers -> LDS buffer
-        const int k0 = c * rs.KC, rows = min(rs.KC, d - k0);
+        const int k0 = k_begin + c * rs.KC, rows = min(rs.KC, k_end - k0);
         char *dst = stage + buf * stage_bytes;
         if (wide) {
 #pragma unroll
@@ -162,7 +163,7 @@ __device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem,
         }
     };
     auto mul = [&](int c, int buf) __attribute__((always_inline)) {
-        const int pieces = min(rs.KC, d - c * rs.KC) / 16;
+        const int pieces = min(rs.KC, k_end - k_begin - c * rs.KC) / 16;
         const char *src = stage + buf * stage_bytes;
         const char *xs = src + x_off + li * rs.XRS + 4 * kq * ES;
         for (int u = part; u < pieces; u += PARTS) {
@@ -180,11 +181,12 @@ __device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem,
         }
     };
 
-    fetch(c_begin);
-    store(c_begin, 0);
+    const int c_end = (k_end - k_begin + rs.KC - 1) / rs.KC;
+    fetch(0);
+    store(0, 0);
     __syncthreads();
-    for (int c = c_begin; c < c_end; ++c) {
-        const int buf = (c - c_begin) & 1;
+    for (int c = 0; c < c_end; ++c) {
+        const int buf = c & 1;
         if (c + 1 < c_end) fetch(c + 1);
         mul(c, buf);
         if (c + 1 < c_end) store(c + 1, buf ^ 1);
@@ -210,30 +212,29 @@ __device__ __forceinline__ void route_logits(const KArgs &a, int t0, char *smem,
     }
 }
 
-// chunks of the reduction a gate task steps through (see RouteShape)
-__host__ __device__ inline int route_chunks(int d, int E, int elem_size) {
-    const RouteShape rs = route_shape(E, elem_size);
-    return (d + rs.KC - 1) / rs.KC;
-}
+// A gate split over its reduction gives every task a slice of whole 16-index pieces, at least
+// kRouteMinSlice indices long: the most slices a reduction of length d can have.
+constexpr int kRouteMinSlice = 128;
+__host__ __device__ inline int route_max_slices(int d) { return d / kRouteMinSlice > 1 ? d / kRouteMinSlice : 1; }
 
 template <typename ET>
-__device__ __forceinline__ void route_logits_dispatch(const KArgs &a, int t0, char *smem, int c0, int c1, bool bias) {
+__device__ __forceinline__ void route_logits_dispatch(const KArgs &a, int t0, char *smem, int k0, int k1, bool bias) {
     const RouteShape rs = route_shape(a.E, (int)sizeof(ET));
     if (rs.parts == 4)
-        route_logits<ET, 1, 4>(a, t0, smem, c0, c1, bias);
+        route_logits<ET, 1, 4>(a, t0, smem, k0, k1, bias);
     else if (rs.parts == 2) {
         if (rs.nbw == 1)
-            route_logits<ET, 1, 2>(a, t0, smem, c0, c1, bias);
+            route_logits<ET, 1, 2>(a, t0, smem, k0, k1, bias);
         else
-            route_logits<ET, 2, 2>(a, t0, smem, c0, c1, bias);
+            route_logits<ET, 2, 2>(a, t0, smem, k0, k1, bias);
     } else if (rs.nbw == 1)
-        route_logits<ET, 1, 1>(a, t0, smem, c0, c1, bias);
+        route_logits<ET, 1, 1>(a, t0, smem, k0, k1, bias);
     else if (rs.nbw == 2)
-        route_logits<ET, 2, 1>(a, t0, smem, c0, c1, bias);
+        route_logits<ET, 2, 1>(a, t0, smem, k0, k1, bias);
     else if (rs.nbw == 3)
-        route_logits<ET, 3, 1>(a, t0, smem, c0, c1, bias);
+        route_logits<ET, 3, 1>(a, t0, smem, k0, k1, bias);
     else
-        route_logits<ET, 4, 1>(a, t0, smem, c0, c1, bias);
+        route_logits<ET, 4, 1>(a, t0, smem, k0, k1, bias);
 }
 
 // ---- bf16 problems inside the megakernel: screen in bf16, decide in fp64 -----
@@ -602,33 +603,60 @@ __device__ __forceinline__ void select_full(const KArgs &a, int t0, const double
 #pragma unroll
         for (int q = 0; q < 4; ++q) v[i][q] = (lane + 64 * q < E) ? lg[tl * E + lane + 64 * q] : NEG;
     }
-    for (int j = 0; j < k; ++j) {
-        double bv[TPW];
-        int bi[TPW];
+    if (E <= 64) {
+        // one logit per lane: its output position is the number of logits that beat it (larger value, or
+        // equal value and lower expert id: the order of the argmax rounds below), counted against
+        // broadcast reads of the row; position j then goes to lane j.  E steps instead of k shuffle trees.
+        int rank[TPW];
 #pragma unroll
-        for (int i = 0; i < TPW; ++i) {
-            bv[i] = v[i][0];
-            bi[i] = lane;
-#pragma unroll
-            for (int q = 1; q < 4; ++q) argmax_merge(bv[i], bi[i], v[i][q], lane + 64 * q);
-        }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
+        for (int i = 0; i < TPW; ++i) rank[i] = lane < E ? 0 : (1 << 20);
+        for (int c = 0; c < E; ++c) {
 #pragma unroll
             for (int i = 0; i < TPW; ++i) {
-                const double ov = __shfl_xor(bv[i], off, 64);
-                const int oi = __shfl_xor(bi[i], off, 64);
-                argmax_merge(bv[i], bi[i], ov, oi);
+                const double ov = lg[(wave + 4 * i) * E + c];
+                rank[i] += (ov > v[i][0] || (ov == v[i][0] && c < lane)) ? 1 : 0;
             }
         }
+        for (int j = 0; j < k; ++j) {
 #pragma unroll
-        for (int i = 0; i < TPW; ++i) {
+            for (int i = 0; i < TPW; ++i) {
+                const int src = __ffsll((long long)__ballot(rank[i] == j)) - 1;
+                const double bv = __shfl(v[i][0], src, 64);
+                if (lane == j) {
+                    my_v[i] = bv;
+                    my_e[i] = src;
+                }
+            }
+        }
+    } else {
+        for (int j = 0; j < k; ++j) {
+            double bv[TPW];
+            int bi[TPW];
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (bi[i] == lane + 64 * q) v[i][q] = NEG;
-            if (lane == j) {
-                my_v[i] = bv[i];
-                my_e[i] = bi[i];
+            for (int i = 0; i < TPW; ++i) {
+                bv[i] = v[i][0];
+                bi[i] = lane;
+#pragma unroll
+                for (int q = 1; q < 4; ++q) argmax_merge(bv[i], bi[i], v[i][q], lane + 64 * q);
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) {
+                    const double ov = __shfl_xor(bv[i], off, 64);
+                    const int oi = __shfl_xor(bi[i], off, 64);
+                    argmax_merge(bv[i], bi[i], ov, oi);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (bi[i] == lane + 64 * q) v[i][q] = NEG;
+                if (lane == j) {
+                    my_v[i] = bv[i];
+                    my_e[i] = bi[i];
+                }
             }
         }
     }
@@ -687,9 +715,10 @@ __device__ __forceinline__ void route_task(const KArgs &a, int task, char *smem,
     if (compute) {
         if (S > 1 || !route_screened_dispatch<ET>(a, t0, smem, my_e)) {
             __shared__ int s_gate_last;
-            const int nchunk = route_chunks(a.d, E, (int)sizeof(ET));
-            route_logits_dispatch<ET>(a, t0, smem, (int)((long long)nchunk * slice / S),
-                                      (int)((long long)nchunk * (slice + 1) / S), S == 1);
+            const int pieces = a.d / 16;  // slice s of S: pieces [pieces * s / S, pieces * (s + 1) / S)
+            route_logits_dispatch<ET>(a, t0, smem, 16 * (int)((long long)pieces * slice / S),
+                                      16 * (int)((long long)pieces * (slice + 1) / S), S == 1);
+            MOE_TT(a.ctrl, 40);
             if (S > 1) {
                 double *lg = (double *)smem;
                 const size_t per = (size_t)kRouteTokens * E;
@@ -703,12 +732,32 @@ __device__ __forceinline__ void route_task(const KArgs &a, int task, char *smem,
                     if (s_gate_last) fence_acquire(0);
                 }
                 __syncthreads();
+                MOE_TT(a.ctrl, 41);
                 if (!s_gate_last) return;
+                // (the partial sums come from memory: all S loads of two logits are issued before the first
+                // addition; one load at a time, the S round trips of a logit would come one after the other)
                 const double *all = a.gate_partial + (size_t)block * S * per;
-                for (int i = threadIdx.x; i < (int)per; i += kThreads) {
-                    double v = a.bias ? (double)a.bias[i % E] : 0.0;
-                    for (int s2 = 0; s2 < S; ++s2) v += all[(size_t)s2 * per + i];
-                    lg[i] = v;
+                constexpr int MAXS = 16, EU = 2;  // S <= MAXS (the host's limit)
+                for (int i0 = threadIdx.x; i0 < (int)per; i0 += kThreads * EU) {
+                    double part[EU][MAXS];
+#pragma unroll
+                    for (int u = 0; u < EU; ++u) {
+                        const int i = min(i0 + u * kThreads, (int)per - 1);
+#pragma unroll
+                        for (int s2 = 0; s2 < MAXS; ++s2)
+                            if (s2 < S) part[u][s2] = all[(size_t)s2 * per + i];
+                    }
+#pragma unroll
+                    for (int u = 0; u < EU; ++u) {
+                        const int i = i0 + u * kThreads;
+                        if (i < (int)per) {
+                            double v = a.bias ? (double)a.bias[i % E] : 0.0;
+#pragma unroll
+                            for (int s2 = 0; s2 < MAXS; ++s2)
+                                if (s2 < S) v += part[u][s2];
+                            lg[i] = v;
+                        }
+                    }
                 }
                 __syncthreads();
             }

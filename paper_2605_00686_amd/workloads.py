@@ -35,6 +35,8 @@ CONFIGS = {
     # DeepSeek-V3-shaped layer with all 256 experts local (Table 1, second shape): every weight tensor has more
     # than 2^31 elements (7.5 GB), which is what this one is for
     "cfg7": dict(T=2048, d=7168, E=256, k=8, f=2048, R=8, dtype="bf16", seed=7, bias_std=0.5),
+    # decode-sized batch on the Qwen3-30B-A3B-shaped layer: few tokens AND many experts
+    "cfg8": dict(T=128, d=2048, E=128, k=8, f=768, R=8, dtype="bf16", seed=8, tile_m=32, bias_std=0.5),
     # --- reduced shapes for parity tests: several tiles plus ragged tails ---
     "mini_f32": dict(T=96, d=192, E=6, k=2, f=320, R=4, dtype="f32", seed=11),
     "mini_bf16": dict(T=384, d=512, E=8, k=2, f=640, R=4, dtype="bf16", seed=12, bias_std=0.5),
