@@ -170,14 +170,14 @@ def test_megakernel_gate_many_experts_and_ties(E):
     dict(T=16, d=64, E=1, k=1, f=64, R=16, dtype="bf16", seed=37, tile_m=32),
     # a decode-sized batch with many experts: the split gate takes precedence over the bf16 screen
     dict(T=128, d=2048, E=128, k=8, f=64, R=8, dtype="bf16", seed=40, tile_m=32, bias_std=0.5),
-    # 128 blocks of 16 tokens, 64 experts: two slices per block
+    # 128 blocks of 16 tokens, 64 experts: half of the workgroups get a gate task (the bf16 screen)
     dict(T=2048, d=1024, E=64, k=2, f=64, R=8, dtype="bf16", seed=41),
     # a single token
     dict(T=1, d=128, E=4, k=2, f=64, R=1, dtype="bf16", seed=38, tile_m=32),
     # a single token, fp32
     dict(T=1, d=64, E=2, k=2, f=64, R=1, dtype="f32", seed=39),
 ], ids=["k_eq_E", "odd_f32", "one_dest", "many_dest", "split_gate", "split_gate_f32", "one_expert",
-        "split_gate_many_experts", "split_gate_128_blocks", "one_token", "one_token_f32"])
+        "split_gate_many_experts", "gate_128_blocks", "one_token", "one_token_f32"])
 @pytest.mark.parametrize("signal_mode", [0, 1])
 def test_megakernel_odd_shapes(cfg, signal_mode):
     B = _binding()
