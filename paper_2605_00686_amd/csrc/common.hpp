@@ -65,6 +65,7 @@ struct KArgs {
     int dtype, tile_m, tile_n, signal_mode, fence_scope;
     int group_size;  // flags per fence group of the per-destination mode, 0 = all flags of a destination
     int scheduler;   // moe_scheduler_t
+    int h_rows_whole_lines;  // f * element size is a multiple of 128 bytes: no cache line of h holds rows of two row blocks
     int gate_split;  // gate tasks per block of 16 tokens: each takes a slice of the reduction (1 = the whole)
     int capacity;    // rows every expert owns in the sorted order, 0 = ragged layout (see moe_problem_t)
     int NP;          // rows of the sorted order: N (ragged) or E * capacity
@@ -153,9 +154,9 @@ __device__ __forceinline__ void fence_acquire(int system_scope) {
 // Acquire without cache invalidation, for data with these three properties:
 // it is written once per launch, its writer made it visible with a device-scope
 // release before the counter or flag that was just observed, and nothing reads
-// its address earlier in the launch.  Then no cache of this XCD can hold a
-// stale copy (caches start a launch empty), and the loads that follow fetch
-// what the writer released.  The fence only keeps the compiler and the
+// its address, or another address in the same 128-byte cache line, earlier in
+// the launch.  Then no cache of this XCD can hold a stale copy (caches start a
+// launch empty), and the loads that follow fetch what the writer released.  The fence only keeps the compiler and the
 // wavefront from moving those loads up.  A device-scope acquire would do the
 // same and also invalidate the XCD's whole L2, which the other workgroups of
 // the XCD are using to share weight tiles.
