@@ -142,6 +142,14 @@ const char *moe_status_string(int status);
  * fence_scope, epoch, group_size and scheduler may change from call to call. */
 int moe_workspace_init(const moe_problem_t *p, void *workspace, void *stream);
 
+/* Test hook for the time-out path (the caller it is for: a test that cannot make a peer fail).  Every wait inside
+ * the kernels is bounded: when its bound expires the waiter records MOE_ERR_TIMEOUT, every other wait sees the
+ * error and gives up, and all workgroups leave in the ordinary way; the status arrives in stats[7] and the
+ * workspace must be initialised again.  This sets the bound, in ticks of the 100 MHz wall clock, for all later calls
+ * on the current device (synchronous; host side: a copy to a device variable); 0 restores the default of 4 s.
+ * Returns MOE_OK or MOE_ERR_HIP. */
+int moe_debug_set_wait_limit(uint64_t ticks);
+
 /*
  * Gate (section 2.1 step 1).  logits[t,e] = sum_i x[t,i] Wg[i,e] + gate_bias[e]
  * accumulated in fp64; topk_idx[t,:] = the k largest in descending order

@@ -22,7 +22,7 @@ MOE_SCHED_STATIC, MOE_SCHED_READY_QUEUE = 0, 1
 MOE_NUM_STATS = 20
 
 EXPORTS = ("moe_workspace_bytes", "moe_num_flags", "moe_status_string", "moe_workspace_init", "moe_route",
-           "moe_dispatch", "moe_megakernel_forward", "moe_combine")
+           "moe_dispatch", "moe_megakernel_forward", "moe_combine", "moe_debug_set_wait_limit")
 
 
 class MoeProblem(ctypes.Structure):
@@ -54,7 +54,9 @@ _lib.moe_route.argtypes = [_pp] + [_vp] * 6
 _lib.moe_dispatch.argtypes = [_pp] + [_vp] * 9
 _lib.moe_megakernel_forward.argtypes = [_pp] + [_vp] * 19
 _lib.moe_combine.argtypes = [_pp] + [_vp] * 7
-for _n in ("moe_workspace_init", "moe_route", "moe_dispatch", "moe_megakernel_forward", "moe_combine"):
+_lib.moe_debug_set_wait_limit.argtypes = [ctypes.c_uint64]
+for _n in ("moe_workspace_init", "moe_route", "moe_dispatch", "moe_megakernel_forward", "moe_combine",
+           "moe_debug_set_wait_limit"):
     getattr(_lib, _n).restype = ctypes.c_int
 
 
@@ -95,6 +97,10 @@ def moe_workspace_bytes(p: MoeProblem) -> int:
 
 def moe_num_flags(p: MoeProblem) -> int:
     return int(_lib.moe_num_flags(ctypes.byref(p)))
+
+
+def moe_debug_set_wait_limit(ticks: int):
+    _check(_lib.moe_debug_set_wait_limit(int(ticks)), "moe_debug_set_wait_limit")
 
 
 def moe_workspace_init(p, workspace, stream=None):

@@ -21,6 +21,10 @@ constexpr int kRouteTokens = 16;    // tokens per gate task
 constexpr int kMaxExperts = 256;    // gate / plan limits
 constexpr int kMaxDest = 1024;
 constexpr u64 kWaitTicks = 400000000ull;  // 4 s of the 100 MHz wall clock: bound of every in-kernel wait
+// The bound the waits use: kWaitTicks unless moe_debug_set_wait_limit() changed it (tests of the time-out path set it to
+// almost nothing, so that the waits give up, the error spreads and every workgroup leaves in the ordinary way).  Read
+// only after a wait has already been spinning.
+__device__ u64 g_wait_ticks = kWaitTicks;
 
 // Control block at the start of the workspace.  All zero between calls: the
 // last workgroup to leave a kernel clears what the kernel dirtied.
@@ -209,7 +213,7 @@ __device__ __forceinline__ bool wait_ge(Ctrl *c, const u32 *p, u32 target) {
                 ok = false;
                 break;
             }
-            if (now_ticks() - t0 > kWaitTicks) {
+            if (now_ticks() - t0 > g_wait_ticks) {
                 set_error(c, MOE_ERR_TIMEOUT);
                 atomicAdd(&c->stats[6], 1ull);
                 ok = false;

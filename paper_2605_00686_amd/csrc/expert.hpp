@@ -757,7 +757,7 @@ __device__ __forceinline__ void combine_task(const KArgs &a, int task) {
                     __builtin_amdgcn_s_sleep(2);
                     if ((++spins & 63) == 0) {
                         if (ld_relaxed_agent(&a.ctrl->error) != 0) break;
-                        if (now_ticks() - t0 > kWaitTicks) {
+                        if (now_ticks() - t0 > g_wait_ticks) {
                             set_error(a.ctrl, MOE_ERR_TIMEOUT);
                             atomicAdd(&a.ctrl->stats[6], 1ull);
                             break;
@@ -888,7 +888,7 @@ __device__ __forceinline__ void ready_queue_stage(const KArgs &a, KArgsAddr karg
                 if (pick == 0) {
                     const u64 now = now_ticks();
                     if (idle_since == 0) idle_since = now;
-                    if (now - idle_since > kWaitTicks) {
+                    if (now - idle_since > g_wait_ticks) {
                         set_error(c, MOE_ERR_TIMEOUT);
                         atomicAdd(&c->stats[6], 1ull);
                         pick = -2;

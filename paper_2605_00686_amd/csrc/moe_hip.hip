@@ -550,6 +550,11 @@ const char *moe_status_string(int s) {
     }
 }
 
+int moe_debug_set_wait_limit(uint64_t ticks) {
+    const u64 v = ticks ? (u64)ticks : kWaitTicks;
+    return hip_ok(hipMemcpyToSymbol(HIP_SYMBOL(g_wait_ticks), &v, sizeof(v)));
+}
+
 size_t moe_workspace_bytes(const moe_problem_t *p) {
     Plan pl;
     if (make_plan(p, &pl) != MOE_OK) return 0;

@@ -581,3 +581,27 @@ def test_repeat_launches_are_bit_identical(scheduler):
             assert int(buf.stats.cpu().numpy()[7]) == 0
             for n in names:
                 assert torch.equal(getattr(buf, n).view(torch.uint8), ref[n].view(torch.uint8)), (c, rep, n)
+
+
+@pytest.mark.parametrize("scheduler", [0, 1])
+def test_expired_waits_drain_the_kernel(scheduler):
+    """The time-out path, forced from the host: with the bound of the in-kernel waits set to one tick, the
+    plan's wait for the gate gives up, the error spreads, every workgroup leaves in the ordinary way and the call
+    reports MOE_ERR_TIMEOUT.  With the bound restored and the workspace initialised again, the same buffers give
+    the right result."""
+    B = _binding()
+    inp = W.make_inputs("mini_bf16")
+    p, buf = run_forward(B, inp, 1, 0, epoch=1, scheduler=scheduler)
+    ref = check_against_oracle(B, inp, p, buf, 1)
+    try:
+        B.moe_debug_set_wait_limit(1)
+        print(f"case mini_bf16 scheduler {scheduler}, wait limit 1 tick", flush=True)
+        p, buf = run_forward(B, inp, 1, 0, epoch=2, buf=buf, scheduler=scheduler)
+        stats = buf.stats.cpu().numpy()
+        assert int(stats[7]) == B.MOE_ERR_TIMEOUT and stats[6] > 0, stats.tolist()
+    finally:
+        B.moe_debug_set_wait_limit(0)
+    B.moe_workspace_init(p, buf.workspace)
+    buf.flags.zero_()
+    p, buf = run_forward(B, inp, 1, 0, epoch=3, buf=buf, scheduler=scheduler)
+    check_against_oracle(B, inp, p, buf, 1, ref)
