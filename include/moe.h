@@ -79,7 +79,9 @@ typedef enum { MOE_SCOPE_AGENT = 0, MOE_SCOPE_SYSTEM = 1 } moe_fence_scope_t;
 typedef enum { MOE_SCHED_STATIC = 0, MOE_SCHED_READY_QUEUE = 1 } moe_scheduler_t;
 
 typedef struct {
-    int32_t T, d, E, k, f, R; /* R must divide T                                   */
+    int32_t T, d, E, k, f, R; /* R must divide T.  Limits (else MOE_ERR_UNSUPPORTED):  */
+                              /* E <= 256, k <= min(E, 32), R <= 1024, T*k <= 2^30,  */
+                              /* d and f multiples of 64 (bf16) or 16 (fp32)         */
     int32_t dtype;            /* moe_dtype_t                                        */
     int32_t tile_m, tile_n;   /* publish tile rows x cols; 0 = 128 x 64 (the tile   */
                               /* of section 2.3).  tile_m in {32,64,128}, tile_n in */

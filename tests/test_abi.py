@@ -71,7 +71,7 @@ def test_invalid_problems_are_rejected_on_the_host(B, kw):
     assert rc == B.MOE_ERR_INVALID_ARG
 
 
-@pytest.mark.parametrize("kw", [dict(d=100), dict(tile_m=48), dict(tile_n=32), dict(E=300, k=2),
+@pytest.mark.parametrize("kw", [dict(d=100), dict(tile_m=48), dict(tile_n=32), dict(E=300, k=2), dict(E=64, k=33), dict(T=2048, R=2048),
                                 # fp32 compute tiles are 64 columns wide: a 128-column publish tile would span two
                                 dict(dtype=0, tile_n=128)])
 def test_unsupported_problems(B, kw):

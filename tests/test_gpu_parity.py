@@ -177,12 +177,14 @@ def test_megakernel_gate_many_experts_and_ties(E):
     # 32 experts per token (the most the interface allows), of 40 and of 256
     dict(T=66, d=128, E=40, k=32, f=64, R=2, dtype="bf16", seed=42, tile_m=64),
     dict(T=48, d=1024, E=256, k=32, f=64, R=3, dtype="bf16", seed=43, bias_std=0.5),
+    # the most destinations the interface allows, one token each
+    dict(T=1024, d=64, E=16, k=2, f=64, R=1024, dtype="bf16", seed=44, tile_m=32),
     # a single token
     dict(T=1, d=128, E=4, k=2, f=64, R=1, dtype="bf16", seed=38, tile_m=32),
     # a single token, fp32
     dict(T=1, d=64, E=2, k=2, f=64, R=1, dtype="f32", seed=39),
 ], ids=["k_eq_E", "odd_f32", "one_dest", "many_dest", "split_gate", "split_gate_f32", "one_expert",
-        "split_gate_many_experts", "gate_128_blocks", "h_rows_share_lines", "k_32_of_40", "k_32_of_256", "one_token", "one_token_f32"])
+        "split_gate_many_experts", "gate_128_blocks", "h_rows_share_lines", "k_32_of_40", "k_32_of_256", "max_dest", "one_token", "one_token_f32"])
 @pytest.mark.parametrize("signal_mode", [0, 1])
 def test_megakernel_odd_shapes(cfg, signal_mode):
     B = _binding()
