@@ -41,7 +41,14 @@ def lib():
         _lib = ctypes.CDLL(build())
         _lib.orc_publish_plan.restype = ctypes.c_int64
         _lib.orc_num_threads.restype = ctypes.c_int
+        _lib.orc_round_bf16.restype = ctypes.c_float
+        _lib.orc_round_bf16.argtypes = [ctypes.c_float]
     return _lib
+
+
+def round_bf16(v: float) -> float:
+    """The rounding the bf16-faithful mode applies (nearest, ties to even), on one fp32 value."""
+    return float(lib().orc_round_bf16(ctypes.c_float(v)))
 
 
 def num_threads() -> int:

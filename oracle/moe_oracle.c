@@ -30,6 +30,11 @@
  * T <= 8, textbook softmax at k = E, numpy bincount / stable argsort for the
  * permutation, a dense numpy SwiGLU MLP at E = 1, identity experts returning
  * x, and the transfer / fence / message-size / FLOP figures the paper prints.
+ * The bf16-faithful mode (section 6.2, "Correctness": the rounding points a
+ * bf16 pipeline cannot avoid) is pinned bit for bit by a numpy rebuild that
+ * rounds with its own integer arithmetic at each point, and round_bf16 by a
+ * table of hand-derived cases (ties to even, carry into the exponent,
+ * negative values).
  * End-to-end numeric values of a whole layer: parity unpinned by the paper (it
  * prints no worked example); pinned only through the special cases above.
  */
@@ -65,6 +70,12 @@ static inline float round_bf16(float f)
         u = (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;
     memcpy(&f, &u, 4);
     return f;
+}
+
+/* round_bf16 as tests call it (so that a table of hand-derived cases can pin it) */
+float orc_round_bf16(float f)
+{
+    return round_bf16(f);
 }
 
 int orc_num_threads(void)

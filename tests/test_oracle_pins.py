@@ -274,6 +274,108 @@ def test_faithful_mode_rounds_to_bf16_and_stays_close():
     assert (np.abs(a["out"] - b["out"]) / scale).max() < 2e-2
 
 
+def _f32(bits):
+    return float(np.array([bits], np.uint32).view(np.float32)[0])
+
+
+# (input bits, expected bf16 bits): derived by hand from the definition "nearest representable value, ties to the
+# one whose last kept bit is 0".  bf16 keeps the upper 16 bits of the fp32 pattern; the lower 16 decide.
+ROUND_BF16_TABLE = [
+    (0x3F800000, 0x3F80),  # 1.0 is representable
+    (0x3F807FFF, 0x3F80),  # just below the midpoint: down
+    (0x3F808001, 0x3F81),  # just above the midpoint: up (truncation would give 0x3F80)
+    (0x3F808000, 0x3F80),  # midpoint, lower neighbour even: down (round-half-up would give 0x3F81)
+    (0x3F818000, 0x3F82),  # midpoint, lower neighbour odd: up to the even one
+    (0x3FFFFFFF, 0x4000),  # mantissa overflows: carry into the exponent, 2.0
+    (0x3FFF8000, 0x4000),  # midpoint below 2.0, lower neighbour odd: carry into the exponent
+    (0x3FFE8000, 0x3FFE),  # midpoint, lower neighbour even: stays
+    (0xBF808000, 0xBF80),  # negative values: the sign does not take part
+    (0xBF818000, 0xBF82),
+    (0xBF808001, 0xBF81),
+    (0xBF807FFF, 0xBF80),
+    (0xC0FFC000, 0xC100),  # -7.9921875 -> -8.0: carry into the exponent, negative
+    (0x00000000, 0x0000),
+    (0x80000000, 0x8000),
+    (0x3A83126F, 0x3A83),  # 0.001: lower half 0x126F < 0x8000, down
+    (0x3DCCCCCD, 0x3DCD),  # 0.1: lower half 0xCCCD > 0x8000, up
+]
+
+
+@pytest.mark.parametrize("bits,want", ROUND_BF16_TABLE)
+def test_round_bf16_table(bits, want):
+    got = np.array([oracle.round_bf16(_f32(bits))], np.float32).view(np.uint32)[0]
+    assert got == (want << 16), f"{bits:#010x} -> {got:#010x}, expected {want << 16:#010x}"
+
+
+def numpy_faithful_layer(x, W1, W3, W2, idx, w):
+    """The layer with the roundings a bf16 matrix-core pipeline cannot avoid (section 6.2, 'Correctness'), rebuilt
+    with numpy matmuls and this file's own integer rounding: g, u rounded to fp32; h = silu(g) * u to bf16; y to
+    fp32, then bf16; out to fp32, then bf16.  Inputs are bf16 bit patterns.  Every dot product here is a sum of
+    products of short mantissas whose exponents span far less than 53 bits, so fp64 sums are exact in any order and
+    the comparison with the oracle can be bit for bit."""
+    xf, W1f, W3f, W2f = (bf16_bits_to_f32(a).astype(np.float64) for a in (x, W1, W3, W2))
+    T, k = idx.shape
+    d = xf.shape[1]
+    staging = np.empty((T * k, d), np.float32)
+    for t in range(T):
+        for j in range(k):
+            e = idx[t, j]
+            g = (xf[t] @ W1f[e]).astype(np.float32).astype(np.float64)
+            u = (xf[t] @ W3f[e]).astype(np.float32).astype(np.float64)
+            h = np.array([gj / (1.0 + math.exp(-gj)) * uj for gj, uj in zip(g, u)], np.float64)
+            h = bf16_bits_to_f32(to_bf16_bits(h.astype(np.float32))).astype(np.float64)
+            y = (h @ W2f[e]).astype(np.float32)
+            staging[t * k + j] = bf16_bits_to_f32(to_bf16_bits(y))
+    acc = (w.astype(np.float64)[:, :, None] * staging.reshape(T, k, d).astype(np.float64)).sum(axis=1)
+    out = bf16_bits_to_f32(to_bf16_bits(acc.astype(np.float32)))
+    return staging, out
+
+
+@pytest.mark.parametrize("T,d,f,E,k,seed", [(16, 64, 96, 4, 2, 23), (9, 32, 48, 3, 3, 24), (12, 128, 64, 5, 1, 25)])
+def test_faithful_mode_bit_exact_against_numpy_rebuild(T, d, f, E, k, seed):
+    r = rng(seed)
+    x = to_bf16_bits(r.standard_normal((T, d)))
+    Wg = to_bf16_bits(r.standard_normal((d, E)) * 0.02)
+    W1 = to_bf16_bits(r.standard_normal((E, d, f)) * 0.1)
+    W3 = to_bf16_bits(r.standard_normal((E, d, f)) * 0.1)
+    W2 = to_bf16_bits(r.standard_normal((E, f, d)) * 0.1)
+    res = oracle.forward(x, Wg, W1, W3, W2, k, faithful=True)
+    st, out = numpy_faithful_layer(x, W1, W3, W2, res["idx"], res["w"])
+    assert np.array_equal(res["staging"].view(np.uint32), st.view(np.uint32))
+    assert np.array_equal(res["out"].view(np.uint32), out.view(np.uint32))
+    # the exact mode differs from it (else the comparison above would say nothing about the roundings)
+    exact = oracle.forward(x, Wg, W1, W3, W2, k)
+    assert not np.array_equal(exact["staging"], st) and not np.array_equal(exact["out"], out)
+    # the token-restricted entry point takes the same roundings
+    tok = np.array(sorted({0, T // 2, T - 1}), np.int32)
+    st_t, out_t = oracle.forward_tokens(x, W1, W3, W2, res["idx"], res["w"], tok, faithful=True)
+    assert np.array_equal(out_t.view(np.uint32), out[tok].view(np.uint32))
+    assert np.array_equal(st_t.reshape(len(tok), k, d).view(np.uint32), st.reshape(T, k, d)[tok].view(np.uint32))
+    # and the stand-alone combine
+    cmb = oracle.combine(st, res["w"], faithful=True)
+    assert np.array_equal(cmb.view(np.uint32), out.view(np.uint32))
+
+
+def test_faithful_rebuild_notices_a_missing_rounding_of_h():
+    """The pin above is sharp: the same rebuild WITHOUT the rounding of h to bf16 (a planted mistake, on the CPU)
+    does not reproduce the oracle's faithful output."""
+    r = rng(23)
+    T, d, f, E, k = 16, 64, 96, 4, 2
+    x = to_bf16_bits(r.standard_normal((T, d)))
+    Wg = to_bf16_bits(r.standard_normal((d, E)) * 0.02)
+    W1 = to_bf16_bits(r.standard_normal((E, d, f)) * 0.1)
+    W3 = to_bf16_bits(r.standard_normal((E, d, f)) * 0.1)
+    W2 = to_bf16_bits(r.standard_normal((E, f, d)) * 0.1)
+    res = oracle.forward(x, Wg, W1, W3, W2, k, faithful=True)
+    xf, W1f, W3f, W2f = (bf16_bits_to_f32(a).astype(np.float64) for a in (x, W1, W3, W2))
+    e = res["idx"][0, 0]
+    g = (xf[0] @ W1f[e]).astype(np.float32).astype(np.float64)
+    u = (xf[0] @ W3f[e]).astype(np.float32).astype(np.float64)
+    h = g / (1.0 + np.exp(-g)) * u  # not rounded
+    y = bf16_bits_to_f32(to_bf16_bits((h @ W2f[e]).astype(np.float32)))
+    assert not np.array_equal(y, res["staging"][0])
+
+
 # ---------------------------------------------------------------- combine
 def test_combine_identity_experts_return_x():
     r = rng(30)
