@@ -92,7 +92,7 @@ def standalone_ops(B, torch, p, buf, dev, cfg, steps):
         ms = timed(lambda: B.moe_route(p, dev["x"], dev["Wg"], dev["gate_bias"], idx2, w2))
         out["moe_route"] = {"ms": ms, "fp64_tflops": 2.0 * T * d * E / (ms * 1e-3) / 1e12}
     ms = timed(lambda: B.moe_dispatch(p, dev["x"], buf.topk_idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm,
-                                      x_perm, buf.workspace))
+                                      x_perm, None, buf.workspace))
     nbytes = 2 * N * d * sz + 12 * N  # rows read and written once, indices read, perm and inv_perm written
     out["moe_dispatch"] = {"ms": ms, "algorithmic_bytes": nbytes, "GB/s": nbytes / (ms * 1e-3) / 1e9,
                            "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}

@@ -90,7 +90,14 @@ typedef struct {
     int32_t signal_mode;      /* moe_signal_mode_t                                  */
     int32_t fence_scope;      /* moe_fence_scope_t                                  */
     uint32_t epoch;           /* value a flag takes when its tile is ready; nonzero */
-                              /* and different from the previous call's             */
+                              /* and larger than that of every earlier call on the  */
+                              /* same `flags` array since the array was last zeroed */
+                              /* (a call only touches the flags of the tiles it     */
+                              /* publishes, and how many those are depends on the   */
+                              /* routing: a flag that an earlier call set and this  */
+                              /* one does not publish keeps its old value, so a     */
+                              /* reused value could read as ready).  To start over, */
+                              /* zero `flags` first                                 */
     int32_t group_size;       /* MOE_SIGNAL_PER_DEST only: flags per fence group    */
                               /* (section 4.1, granularity of Algorithm 1).  0 = all */
                               /* flags of a destination form one group (the paper's */
@@ -109,6 +116,15 @@ typedef struct {
                               /* -1 in unused ones, x_perm has E*C rows (unused:    */
                               /* zero).  Nothing is dropped: an expert with more    */
                               /* than C rows is an error (MOE_ERR_CAPACITY)         */
+    uint32_t wait_ticks;      /* bound of every wait inside the kernels, in ticks   */
+                              /* of the GPU's 100 MHz wall clock; 0 = 4 s.  When a  */
+                              /* wait's bound expires the waiter records            */
+                              /* MOE_ERR_TIMEOUT, every other wait sees the error   */
+                              /* and gives up, and all workgroups leave in the      */
+                              /* ordinary way; the status arrives in stats[7] and   */
+                              /* the workspace must be initialised again.  (A tiny  */
+                              /* value is how a test forces that path from the      */
+                              /* host.)                                             */
 } moe_problem_t;
 
 /* number of 64-bit counters moe_megakernel_forward writes to `stats` */
@@ -122,7 +138,8 @@ typedef struct {
  * stats[8..13] in-kernel timeline: nanoseconds from the first task drawn to the end of
  *   the last gate task [8], the plan [9], the last permutation block [10], the last
  *   GEMM1 tile [11], the last GEMM2 tile [12], the last combine task [13]
- * stats[14] nanoseconds workgroups spent waiting on dependencies, summed over workgroups
+ * stats[14] nanoseconds workgroups spent waiting on dependencies (each wait counted once per
+ *   workgroup, by its clock from the first poll to the last), summed over workgroups
  * stats[15] workgroups launched
  * stats[16..17] MOE_SCHED_READY_QUEUE only (else 0): tasks taken from the ready queues [16];
  *   GEMM2 tiles among them that a workgroup ran while GEMM1 tiles were still waiting to be
@@ -143,14 +160,6 @@ const char *moe_status_string(int status);
  * depend on T, d, E, k, f, R, dtype, tile_m, tile_n and capacity only: signal_mode,
  * fence_scope, epoch, group_size and scheduler may change from call to call. */
 int moe_workspace_init(const moe_problem_t *p, void *workspace, void *stream);
-
-/* Test hook for the time-out path (the caller it is for: a test that cannot make a peer fail).  Every wait inside
- * the kernels is bounded: when its bound expires the waiter records MOE_ERR_TIMEOUT, every other wait sees the
- * error and gives up, and all workgroups leave in the ordinary way; the status arrives in stats[7] and the
- * workspace must be initialised again.  This sets the bound, in ticks of the 100 MHz wall clock, for all later calls
- * on the current device (synchronous; host side: a copy to a device variable); 0 restores the default of 4 s.
- * Returns MOE_OK or MOE_ERR_HIP. */
-int moe_debug_set_wait_limit(uint64_t ticks);
 
 /*
  * Gate (section 2.1 step 1).  logits[t,e] = sum_i x[t,i] Wg[i,e] + gate_bias[e]
@@ -174,10 +183,15 @@ int moe_route(const moe_problem_t *p, const void *x, const void *Wg, const float
  *   With p->capacity = C > 0, perm and x_perm have E*C entries / rows (see
  *   moe_problem_t) and inv_perm[s] = e*C + rank; counts are exact whatever C is,
  *   and when one exceeds C nothing else is written.
+ *   status_dev: int32 on the device, may be NULL, written only on failure:
+ *   MOE_ERR_BAD_ROUTING if an id lies outside [0,E) (such a slot is counted for
+ *   no expert), MOE_ERR_CAPACITY if an expert has more than C rows.  In both
+ *   cases counts (and offsets) are written, perm / inv_perm / x_perm are not,
+ *   and no slot number is ever followed outside x.
  */
 int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx, int32_t *counts,
                  int32_t *offsets, int32_t *perm, int32_t *inv_perm, void *x_perm,
-                 void *workspace, void *stream);
+                 int32_t *status_dev, void *workspace, void *stream);
 
 /*
  * The whole layer in ONE persistent kernel (sections 2.1, 2.3, 4.1): gate,

@@ -22,7 +22,7 @@ MOE_SCHED_STATIC, MOE_SCHED_READY_QUEUE = 0, 1
 MOE_NUM_STATS = 20
 
 EXPORTS = ("moe_workspace_bytes", "moe_num_flags", "moe_status_string", "moe_workspace_init", "moe_route",
-           "moe_dispatch", "moe_megakernel_forward", "moe_combine", "moe_debug_set_wait_limit")
+           "moe_dispatch", "moe_megakernel_forward", "moe_combine")
 
 
 class MoeProblem(ctypes.Structure):
@@ -30,7 +30,8 @@ class MoeProblem(ctypes.Structure):
                                               "signal_mode", "fence_scope")] + [("epoch", ctypes.c_uint32),
                                                                                  ("group_size", ctypes.c_int32),
                                                                                  ("scheduler", ctypes.c_int32),
-                                                                                 ("capacity", ctypes.c_int32)]
+                                                                                 ("capacity", ctypes.c_int32),
+                                                                                 ("wait_ticks", ctypes.c_uint32)]
 
 
 class MoeError(RuntimeError):
@@ -51,23 +52,21 @@ _lib.moe_status_string.restype = ctypes.c_char_p
 _lib.moe_status_string.argtypes = [ctypes.c_int]
 _lib.moe_workspace_init.argtypes = [_pp, _vp, _vp]
 _lib.moe_route.argtypes = [_pp] + [_vp] * 6
-_lib.moe_dispatch.argtypes = [_pp] + [_vp] * 9
+_lib.moe_dispatch.argtypes = [_pp] + [_vp] * 10
 _lib.moe_megakernel_forward.argtypes = [_pp] + [_vp] * 19
 _lib.moe_combine.argtypes = [_pp] + [_vp] * 7
-_lib.moe_debug_set_wait_limit.argtypes = [ctypes.c_uint64]
-for _n in ("moe_workspace_init", "moe_route", "moe_dispatch", "moe_megakernel_forward", "moe_combine",
-           "moe_debug_set_wait_limit"):
+for _n in ("moe_workspace_init", "moe_route", "moe_dispatch", "moe_megakernel_forward", "moe_combine"):
     getattr(_lib, _n).restype = ctypes.c_int
 
 
 def problem(T, d, E, k, f, R, dtype, tile_m=0, tile_n=0, signal_mode=MOE_SIGNAL_PER_DEST,
-            fence_scope=MOE_SCOPE_AGENT, epoch=1, group_size=0, scheduler=0, capacity=0) -> MoeProblem:
+            fence_scope=MOE_SCOPE_AGENT, epoch=1, group_size=0, scheduler=0, capacity=0, wait_ticks=0) -> MoeProblem:
     if isinstance(dtype, torch.dtype):
         dtype = MOE_DT_F32 if dtype == torch.float32 else MOE_DT_BF16
     elif isinstance(dtype, str):
         dtype = MOE_DT_F32 if dtype == "f32" else MOE_DT_BF16
     return MoeProblem(T, d, E, k, f, R, dtype, tile_m, tile_n, signal_mode, fence_scope, epoch, group_size, scheduler,
-                      capacity)
+                      capacity, wait_ticks)
 
 
 def _ptr(t):
@@ -99,10 +98,6 @@ def moe_num_flags(p: MoeProblem) -> int:
     return int(_lib.moe_num_flags(ctypes.byref(p)))
 
 
-def moe_debug_set_wait_limit(ticks: int):
-    _check(_lib.moe_debug_set_wait_limit(int(ticks)), "moe_debug_set_wait_limit")
-
-
 def moe_workspace_init(p, workspace, stream=None):
     _check(_lib.moe_workspace_init(ctypes.byref(p), _ptr(workspace), _stream(stream)), "moe_workspace_init")
 
@@ -112,9 +107,10 @@ def moe_route(p, x, Wg, gate_bias, topk_idx, topk_w, stream=None):
                           _stream(stream)), "moe_route")
 
 
-def moe_dispatch(p, x, topk_idx, counts, offsets, perm, inv_perm, x_perm, workspace, stream=None):
+def moe_dispatch(p, x, topk_idx, counts, offsets, perm, inv_perm, x_perm, status_dev, workspace, stream=None):
     _check(_lib.moe_dispatch(ctypes.byref(p), _ptr(x), _ptr(topk_idx), _ptr(counts), _ptr(offsets), _ptr(perm),
-                             _ptr(inv_perm), _ptr(x_perm), _ptr(workspace), _stream(stream)), "moe_dispatch")
+                             _ptr(inv_perm), _ptr(x_perm), _ptr(status_dev), _ptr(workspace), _stream(stream)),
+           "moe_dispatch")
 
 
 def moe_megakernel_forward(p, x, Wg, gate_bias, W1, W3, W2, topk_idx, topk_w, counts, offsets, perm, inv_perm,

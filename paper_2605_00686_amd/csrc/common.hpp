@@ -20,11 +20,9 @@ constexpr int kPermBlock = 64;      // tokens per permutation block (one bit eac
 constexpr int kRouteTokens = 16;    // tokens per gate task
 constexpr int kMaxExperts = 256;    // gate / plan limits
 constexpr int kMaxDest = 1024;
-constexpr u64 kWaitTicks = 400000000ull;  // 4 s of the 100 MHz wall clock: bound of every in-kernel wait
-// The bound the waits use: kWaitTicks unless moe_debug_set_wait_limit() changed it (tests of the time-out path set it to
-// almost nothing, so that the waits give up, the error spreads and every workgroup leaves in the ordinary way).  Read
-// only after a wait has already been spinning.
-__device__ u64 g_wait_ticks = kWaitTicks;
+constexpr u64 kWaitTicks = 400000000ull;  // 4 s of the 100 MHz wall clock: default bound of every in-kernel wait
+// (the bound a call uses is KArgs::wait_ticks, from moe_problem_t::wait_ticks: tests of the time-out path set it to
+// almost nothing, so that the waits give up, the error spreads and every workgroup leaves in the ordinary way)
 
 // Control block at the start of the workspace.  All zero between calls: the
 // last workgroup to leave a kernel clears what the kernel dirtied.
@@ -74,6 +72,7 @@ struct KArgs {
     int capacity;    // rows every expert owns in the sorted order, 0 = ragged layout (see moe_problem_t)
     int NP;          // rows of the sorted order: N (ragged) or E * capacity
     u32 epoch;
+    u64 wait_ticks;  // bound of every in-kernel wait, in ticks of the 100 MHz wall clock
     int N, per_dest, ncb;  // slots, tokens per destination, column blocks per row
     int nPB, nRT, nCT;     // permutation blocks, gate tasks, combine tasks
     int comb_tokens;       // tokens per combine task
@@ -191,10 +190,11 @@ __device__ __forceinline__ void sync_stores() {
 
 // Spin until *p >= target (agent scope), bounded by the wall clock and by the
 // global error flag so that a broken dependency drains the grid instead of
-// hanging it.  Called by one thread; returns false on time-out.  INVALIDATE
+// hanging it.  Called by one thread; returns false on time-out; `limit` is the
+// bound in wall-clock ticks.  INVALIDATE
 // false: see fence_acquire_no_invalidate().
 template <bool INVALIDATE = true>
-__device__ __forceinline__ bool wait_ge(Ctrl *c, const u32 *p, u32 target) {
+__device__ __forceinline__ bool wait_ge(Ctrl *c, const u32 *p, u32 target, u64 limit) {
     if (ld_relaxed_agent(p) >= target) {
         if (INVALIDATE)
             fence_acquire(0);
@@ -213,7 +213,7 @@ __device__ __forceinline__ bool wait_ge(Ctrl *c, const u32 *p, u32 target) {
                 ok = false;
                 break;
             }
-            if (now_ticks() - t0 > g_wait_ticks) {
+            if (now_ticks() - t0 > limit) {
                 set_error(c, MOE_ERR_TIMEOUT);
                 atomicAdd(&c->stats[6], 1ull);
                 ok = false;

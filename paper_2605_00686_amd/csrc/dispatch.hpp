@@ -339,6 +339,7 @@ __device__ __forceinline__ void block_perm_task(const KArgs &a, int b, const int
         if (lane == 0) off[E] = total;
     }
     __syncthreads();
+    const int total_rows = off[E];
     __shared__ int s_over;
     if (tid == 0) s_over = 0;
     __syncthreads();
@@ -350,13 +351,24 @@ __device__ __forceinline__ void block_perm_task(const KArgs &a, int b, const int
         __syncthreads();
     }
     for (int e = tid; e < E; e += kThreads) base[e] += off[e];
-    if (b == 0)
+    // ids outside [0, E) are counted nowhere: the histogram then accounts for fewer than N slots
+    const bool bad_ids = total_rows != a.N;
+    if (b == 0) {
         for (int e = tid; e <= E; e += kThreads) {
             a.offsets[e] = off[e];
             if (e < E) a.counts[e] = tot[e];
         }
+        if (tid == 0 && a.status_dev) {
+            if (bad_ids)
+                *a.status_dev = (int)MOE_ERR_BAD_ROUTING;
+            else if (s_over)
+                *a.status_dev = (int)MOE_ERR_CAPACITY;
+        }
+    }
     __syncthreads();
-    if (s_over) return;  // an expert has more rows than the capacity: counts say so, nothing else is written
+    // an expert has more rows than the capacity, or an id is invalid: counts and the status say so, nothing else
+    // is written
+    if (s_over || bad_ids) return;
     perm_task<ET>(a, b, mask_smem, base, tot);
 }
 
@@ -369,7 +381,7 @@ __device__ void gather_rows(const KArgs &a, int first, int stride, size_t row_by
     for (int p = first; p < a.NP; p += stride) {
         const int s = a.perm[p];
         uint4 *dst = (uint4 *)((char *)a.x_perm + (size_t)p * row_bytes);
-        if (s < 0) {  // unused row of the padded layout
+        if (s < 0 || s >= a.N) {  // unused row of the padded layout (a slot number is never followed out of x)
             for (int c = lane; c < pieces; c += 64) dst[c] = make_uint4(0u, 0u, 0u, 0u);
             continue;
         }

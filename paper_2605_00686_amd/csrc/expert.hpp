@@ -594,8 +594,8 @@ static __device__ __attribute__((noinline)) void tile_stage(KArgsAddr args, u32 
                 // then is an invalidating acquire needed
                 const bool lines = a.h_rows_whole_lines != 0;
                 if (tid == 0) {
-                    sl->ok = (single || (lines ? wait_ge<false>(c, &a.h_ready[ti.rb], (u32)a.tl.NT1)
-                                               : wait_ge<true>(c, &a.h_ready[ti.rb], (u32)a.tl.NT1)))
+                    sl->ok = (single || (lines ? wait_ge<false>(c, &a.h_ready[ti.rb], (u32)a.tl.NT1, a.wait_ticks)
+                                               : wait_ge<true>(c, &a.h_ready[ti.rb], (u32)a.tl.NT1, a.wait_ticks)))
                                  ? 1
                                  : 0;
                 }
@@ -742,6 +742,7 @@ __device__ __forceinline__ void combine_task(const KArgs &a, int task) {
         const int per_tok = k * a.ncb;
         const int nflag = nt * per_tok;
         bool ok = true;
+        const u64 tw0 = WAIT ? now_ticks() : 0ull;
 #pragma unroll 4
         for (int q = tid; q < nflag; q += kThreads) {
             const int slot = t_first * k + q / a.ncb;
@@ -757,19 +758,20 @@ __device__ __forceinline__ void combine_task(const KArgs &a, int task) {
                     __builtin_amdgcn_s_sleep(2);
                     if ((++spins & 63) == 0) {
                         if (ld_relaxed_agent(&a.ctrl->error) != 0) break;
-                        if (now_ticks() - t0 > g_wait_ticks) {
+                        if (now_ticks() - t0 > a.wait_ticks) {
                             set_error(a.ctrl, MOE_ERR_TIMEOUT);
                             atomicAdd(&a.ctrl->stats[6], 1ull);
                             break;
                         }
                     }
                 }
-                atomicAdd(&a.ctrl->stats[14], now_ticks() - t0);
             }
         }
         fence_acquire(sys);
         if (!WAIT && !ok && a.status_dev) atomicExch(a.status_dev, (int)MOE_ERR_NOT_READY);
-        __syncthreads();  // rows guarded by flags another lane polled
+        // rows guarded by flags another lane polled; the time the workgroup waited is added once
+        const int waited = __syncthreads_or(WAIT && !ok);
+        if (WAIT && waited && tid == 0) atomicAdd(&a.ctrl->stats[14], now_ticks() - tw0);
     }
     const size_t rstride = (size_t)a.d * sizeof(ET);
     for (int tt = wave; tt < nt; tt += 4) {
@@ -888,7 +890,7 @@ __device__ __forceinline__ void ready_queue_stage(const KArgs &a, KArgsAddr karg
                 if (pick == 0) {
                     const u64 now = now_ticks();
                     if (idle_since == 0) idle_since = now;
-                    if (now - idle_since > g_wait_ticks) {
+                    if (now - idle_since > a.wait_ticks) {
                         set_error(c, MOE_ERR_TIMEOUT);
                         atomicAdd(&c->stats[6], 1ull);
                         pick = -2;

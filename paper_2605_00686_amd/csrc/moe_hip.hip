@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstring>
+#include <mutex>
 #include <type_traits>
 
 #include "common.hpp"
@@ -49,18 +50,30 @@ __global__ __launch_bounds__(kThreads) void k_block_perm(KArgs a) {
 }
 
 __global__ __launch_bounds__(kThreads) void k_gather(KArgs a, size_t row_bytes) {
-    if (a.ctrl->error != 0) return;
-    if (a.capacity > 0) {  // padded layout: an expert over its capacity means perm was not written
-        int over = 0;
-        for (int e = threadIdx.x; e < a.E; e += kThreads) over |= a.counts[e] > a.capacity;
-        if (__syncthreads_or(over)) return;
+    if (a.ctrl && a.ctrl->error != 0) return;  // (no control block: the form without a workspace)
+    // perm was not written if an expert is over its capacity (padded layout) or if the histogram does not account
+    // for every slot (an expert id outside [0, E)): nothing is gathered then
+    __shared__ int s_rows;
+    if (threadIdx.x == 0) s_rows = 0;
+    __syncthreads();
+    int over = 0, mine = 0;
+    for (int e = threadIdx.x; e < a.E; e += kThreads) {
+        const int c = a.counts[e];
+        mine += c;
+        over |= (a.capacity > 0 && c > a.capacity) ? 1 : 0;
     }
+    if (mine) atomicAdd(&s_rows, mine);
+    if (__syncthreads_or(over)) return;
+    if (s_rows != a.N) return;
     const int wave = (blockIdx.x * kThreads + threadIdx.x) >> 6;
     gather_rows(a, wave, (gridDim.x * kThreads) >> 6, row_bytes);
 }
 
 // standalone dispatch leaves the control block clean for the next call
 __global__ __launch_bounds__(kThreads) void k_dispatch_finish(KArgs a) {
+    // (one workgroup: the status must be read before the control block is cleared)
+    if (threadIdx.x == 0 && a.status_dev && a.ctrl->error != 0) *a.status_dev = -(int)a.ctrl->error;
+    __syncthreads();
     u32 *z = (u32 *)a.ctrl;
     const size_t n = a.zero_bytes / 4;
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
@@ -104,7 +117,7 @@ __device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
         } else if (task < a.t_plan) {
             phase = 0;
             if (a.t_gate > 0 && !seen_wgt) {  // the transposed gate weights are complete
-                if (tid == 0) sl->ok = wait_ge(c, &c->wgt_done, (u32)a.t_gate) ? 1 : 0;
+                if (tid == 0) sl->ok = wait_ge(c, &c->wgt_done, (u32)a.t_gate, a.wait_ticks) ? 1 : 0;
                 __syncthreads();
                 seen_wgt = true;
                 bad = bad || !sl->ok;
@@ -120,7 +133,7 @@ __device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
             }
         } else if (task < a.t_perm) {
             phase = 1;
-            if (tid == 0) sl->ok = wait_ge(c, &c->route_done, (u32)a.nRT) ? 1 : 0;
+            if (tid == 0) sl->ok = wait_ge(c, &c->route_done, (u32)a.nRT, a.wait_ticks) ? 1 : 0;
             __syncthreads();
 #ifdef MOE_TILE_TIMING
             if (tid == 0) c->dbg[39] = now_ticks() - c->t0;
@@ -134,7 +147,7 @@ __device__ __forceinline__ int front_stage(const KArgs &a, char *smem) {
         } else {
             phase = 2;
             if (!seen_plan) {
-                if (tid == 0) sl->ok = (wait_ge(c, &c->plan_done, 1u) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
+                if (tid == 0) sl->ok = (wait_ge(c, &c->plan_done, 1u, a.wait_ticks) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
                 __syncthreads();
                 seen_plan = true;
                 bad = bad || !sl->ok;
@@ -194,7 +207,7 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
 
     // ---- wait for the plan and the permutation (and with them for every gate task); copy
     // the decode tables to LDS
-    if (tid == 0) s_ok = (wait_ge(c, &c->plan_done, 1u) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
+    if (tid == 0) s_ok = (wait_ge(c, &c->plan_done, 1u, a.wait_ticks) && ld_relaxed_agent(&c->error) == 0) ? 1 : 0;
     __syncthreads();
     bad = bad || !s_ok;
     int n_rb = 0, n_rbs = 0;
@@ -219,7 +232,7 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
         }
     }
     __syncthreads();
-    if (tid == 0) s_ok = wait_ge(c, &c->perm_done, (u32)a.nPB) ? 1 : 0;
+    if (tid == 0) s_ok = wait_ge(c, &c->perm_done, (u32)a.nPB, a.wait_ticks) ? 1 : 0;
     __syncthreads();
     bad = bad || !s_ok;
 
@@ -276,30 +289,8 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
         }
         __syncthreads();
 #ifdef MOE_TILE_TIMING
-        if (tid == 0) {
-            const double n1 = (double)c->stats[4], n2 = (double)c->stats[5];
-            printf("tile timing (us/tile): g1 n=%.0f pre %.2f call %.2f [gemm %.2f store %.2f release %.2f] | g2 n=%.0f wait %.2f call %.2f "
-                   "[gemm %.2f publish %.2f (rows %.2f copy %.2f signal %.2f)] | finish %.2f\n",
-                   n1, c->dbg[0] / n1 / 100., c->dbg[4] / n1 / 100., c->dbg[1] / n1 / 100., c->dbg[2] / n1 / 100., c->dbg[3] / n1 / 100., n2,
-                   c->dbg[5] / n2 / 100., c->dbg[9] / n2 / 100., c->dbg[7] / n2 / 100., c->dbg[8] / n2 / 100., c->dbg[11] / n2 / 100.,
-                   c->dbg[12] / n2 / 100., c->dbg[13] / n2 / 100., c->dbg[10] / (n1 + n2) / 100.);
-            printf("gate (us/task, thread 0): logits %.2f, top-k and histograms %.2f\n", c->dbg[32] / (double)a.nRT / 100.,
-                   c->dbg[33] / (double)a.nRT / 100.);
-            printf("screened gate (us/task): screen %.2f, candidates %.2f, exact %.2f, select %.2f; fallbacks %llu\n",
-                   c->dbg[40] / (double)a.nRT / 100., c->dbg[41] / (double)a.nRT / 100., c->dbg[42] / (double)a.nRT / 100.,
-                   c->dbg[43] / (double)a.nRT / 100., c->dbg[44]);
-            printf("last transposition task ends at %.2f us, last gate task starts at %.2f us; ", c->dbg[46] / 100., c->dbg[45] / 100.);
-            printf("plan starts at %.2f us; ", c->dbg[39] / 100.);
-            printf("plan (us): stage %.2f, expert scans %.2f, block scan %.2f, flags %.2f, write-back %.2f\n", c->dbg[34] / 100.,
-                   c->dbg[35] / 100., c->dbg[36] / 100., c->dbg[37] / 100., c->dbg[38] / 100.);
-            printf("stage calls (us per workgroup): g1 big %.1f, g1 small %.1f, g2 big %.1f, g2 small %.1f\n", c->dbg[20] / (double)gridDim.x / 100.,
-                   c->dbg[21] / (double)gridDim.x / 100., c->dbg[22] / (double)gridDim.x / 100., c->dbg[23] / (double)gridDim.x / 100.);
-            printf("tiles done (us): avg over workgroups %.1f, last %.1f; per queue g1 end", c->dbg[14] / (double)gridDim.x / 100., c->dbg[15] / 100.);
-            for (int q = 0; q < 8; ++q) printf(" %.0f", c->dbg[16 + q] / 100.);
-            printf("; g2 end");
-            for (int q = 0; q < 8; ++q) printf(" %.0f", c->dbg[24 + q] / 100.);
-            printf("\n");
-        }
+        // development build: the per-part tick sums follow the statistics (the caller's array has room for them)
+        if (a.stats && tid < 48) a.stats[MOE_NUM_STATS + tid] = c->dbg[tid];
         __syncthreads();
 #endif
         u32 *z = (u32 *)c;
@@ -308,6 +299,8 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
 }
 
 // --------------------------------------------------------------- host side
+constexpr int kMaxDevices = 16;  // devices the host-side launch memo covers (others ask the runtime on every call)
+
 static inline size_t align_up(size_t v, size_t al) { return (v + al - 1) / al * al; }
 
 static int elem_size(int dtype) { return dtype == MOE_DT_F32 ? 4 : 2; }
@@ -442,6 +435,7 @@ static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
     a->dtype = p.dtype; a->tile_m = pl.tile_m; a->tile_n = pl.tile_n;
     a->signal_mode = p.signal_mode; a->fence_scope = p.fence_scope; a->epoch = p.epoch;
     a->group_size = p.group_size;
+    a->wait_ticks = p.wait_ticks ? (u64)p.wait_ticks : kWaitTicks;
     a->scheduler = p.scheduler;
     a->h_rows_whole_lines = ((size_t)p.f * elem_size(p.dtype)) % 128 == 0 ? 1 : 0;
     a->N = pl.N; a->NP = pl.NP; a->capacity = p.capacity; a->per_dest = pl.per_dest; a->ncb = pl.ncb;
@@ -488,12 +482,37 @@ static int check_ws(const void *ws) {
 
 static int hip_ok(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_HIP; }
 
+// Allow `kernel` `bytes` of dynamic LDS on the current device.  The limit of a kernel is only ever raised, and
+// what it was raised to is remembered per (device, kernel), so that a call which needs no more than an earlier
+// one asks the runtime nothing (a host-side memo: no device state, nothing a call can observe).
+static int set_smem_raw(const void *kernel, size_t bytes) {
+    if (bytes > 160 * 1024) return MOE_ERR_UNSUPPORTED;
+    if (bytes <= 48 * 1024) return MOE_OK;
+    struct Entry {
+        int dev;
+        const void *kernel;
+        size_t limit;
+    };
+    static std::mutex lock;
+    static Entry table[64];
+    static int n = 0;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
+    std::lock_guard<std::mutex> g(lock);
+    Entry *hit = nullptr;
+    for (int i = 0; i < n; ++i)
+        if (table[i].dev == dev && table[i].kernel == kernel) hit = &table[i];
+    if (hit && hit->limit >= bytes) return MOE_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) return MOE_ERR_HIP;
+    if (hit)
+        hit->limit = bytes;
+    else if (n < 64)
+        table[n++] = Entry{dev, kernel, bytes};
+    return MOE_OK;
+}
 template <class K>
 static int set_smem(K kernel, size_t bytes) {
-    if (bytes > 160 * 1024) return MOE_ERR_UNSUPPORTED;
-    if (bytes > 48 * 1024)
-        return hip_ok(hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
-    return MOE_OK;
+    return set_smem_raw((const void *)kernel, bytes);
 }
 
 template <class P, class PS>
@@ -517,10 +536,30 @@ static int launch_mega(const Plan &pl, const KArgs &a_in, hipStream_t st) {
     auto kern = k_megakernel<P, PS>;
     int rc = set_smem(kern, smem);
     if (rc) return rc;
+    // The CU count and the occupancy of this kernel are asked for once per device and LDS size (a host-side memo
+    // of what the runtime answered, like the one in set_smem_raw).
+    struct Memo {
+        size_t smem;
+        int cus, per_cu;
+    };
+    static std::mutex memo_lock;
+    static Memo memo[kMaxDevices][4];
+    static int memo_n[kMaxDevices];
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return MOE_ERR_HIP;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kThreads, smem) != hipSuccess) return MOE_ERR_HIP;
+    const bool memoised = dev >= 0 && dev < kMaxDevices;
+    bool found = false;
+    if (memoised) {
+        std::lock_guard<std::mutex> g(memo_lock);
+        for (int i = 0; i < memo_n[dev]; ++i)
+            if (memo[dev][i].smem == smem) cus = memo[dev][i].cus, per_cu = memo[dev][i].per_cu, found = true;
+    }
+    if (!found) {
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return MOE_ERR_HIP;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, kThreads, smem) != hipSuccess) return MOE_ERR_HIP;
+        std::lock_guard<std::mutex> g(memo_lock);
+        if (memoised && memo_n[dev] < 4) memo[dev][memo_n[dev]++] = Memo{smem, cus, per_cu};
+    }
     if (per_cu < 1) return MOE_ERR_UNSUPPORTED;
     if (per_cu > 2) per_cu = 2;
     long long grid = (long long)cus * per_cu;
@@ -548,11 +587,6 @@ const char *moe_status_string(int s) {
         case MOE_ERR_CAPACITY: return "an expert received more rows than the capacity";
         default: return "unknown status";
     }
-}
-
-int moe_debug_set_wait_limit(uint64_t ticks) {
-    const u64 v = ticks ? (u64)ticks : kWaitTicks;
-    return hip_ok(hipMemcpyToSymbol(HIP_SYMBOL(g_wait_ticks), &v, sizeof(v)));
 }
 
 size_t moe_workspace_bytes(const moe_problem_t *p) {
@@ -598,19 +632,11 @@ int moe_route(const moe_problem_t *p, const void *x, const void *Wg, const float
     return hip_ok(hipGetLastError());
 }
 
-int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx, int32_t *counts, int32_t *offsets,
-                 int32_t *perm, int32_t *inv_perm, void *x_perm, void *workspace, void *stream) {
-    Plan pl;
-    int rc = make_plan(p, &pl);
-    if (rc) return rc;
-    if (!topk_idx || !counts || !offsets || !perm || !inv_perm) return MOE_ERR_INVALID_ARG;
-    if (x_perm && !x) return MOE_ERR_INVALID_ARG;
-    if ((rc = check_ws(workspace))) return rc;
-    KArgs a;
-    fill_args(pl, workspace, &a);
-    a.x = x; a.idx = const_cast<int32_t *>(topk_idx);
-    a.counts = counts; a.offsets = offsets; a.perm = perm; a.inv_perm = inv_perm; a.x_perm = x_perm;
-    hipStream_t st = (hipStream_t)stream;
+// The launches of a dispatch.  `short_only`: the form that needs the control block and the plan's tables is not
+// available (no workspace).
+static int dispatch_launches(const Plan &pl, const KArgs &a, bool short_only, hipStream_t st) {
+    const moe_problem_t *p = &pl.p;
+    int rc;
     const size_t row_bytes = (size_t)p->d * elem_size(p->dtype);
     int ggrid = (pl.NP + 3) / 4;  // gather: one wavefront per row while rows last
     if (ggrid > 8192) ggrid = 8192;
@@ -626,9 +652,10 @@ int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx,
             if ((rc = set_smem(k_block_perm<bf16_t>, bsmem))) return rc;
             hipLaunchKernelGGL(k_block_perm<bf16_t>, dim3(pl.nPB), dim3(kThreads), bsmem, st, a);
         }
-        if (x_perm) hipLaunchKernelGGL(k_gather, dim3(ggrid), dim3(kThreads), 0, st, a, row_bytes);
+        if (a.x_perm) hipLaunchKernelGGL(k_gather, dim3(ggrid), dim3(kThreads), 0, st, a, row_bytes);
         return hip_ok(hipGetLastError());
     }
+    if (short_only) return MOE_ERR_UNSUPPORTED;
     const size_t psmem = plan_smem(pl);
     if ((rc = set_smem(k_plan, psmem))) return rc;
     // histogram (gate task without the gate), plan, permutation, row gather, clean-up
@@ -641,9 +668,25 @@ int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx,
         hipLaunchKernelGGL(k_plan, dim3(1), dim3(kThreads), psmem, st, a);
         hipLaunchKernelGGL(k_perm<bf16_t>, dim3(pl.nPB), dim3(kThreads), (size_t)p->E * 8, st, a);
     }
-    if (x_perm) hipLaunchKernelGGL(k_gather, dim3(ggrid), dim3(kThreads), 0, st, a, row_bytes);
-    hipLaunchKernelGGL(k_dispatch_finish, dim3(16), dim3(kThreads), 0, st, a);
+    if (a.x_perm) hipLaunchKernelGGL(k_gather, dim3(ggrid), dim3(kThreads), 0, st, a, row_bytes);
+    hipLaunchKernelGGL(k_dispatch_finish, dim3(1), dim3(kThreads), 0, st, a);
     return hip_ok(hipGetLastError());
+}
+
+int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx, int32_t *counts, int32_t *offsets,
+                 int32_t *perm, int32_t *inv_perm, void *x_perm, int32_t *status_dev, void *workspace, void *stream) {
+    Plan pl;
+    int rc = make_plan(p, &pl);
+    if (rc) return rc;
+    if (!topk_idx || !counts || !offsets || !perm || !inv_perm) return MOE_ERR_INVALID_ARG;
+    if (x_perm && !x) return MOE_ERR_INVALID_ARG;
+    if ((rc = check_ws(workspace))) return rc;
+    KArgs a;
+    fill_args(pl, workspace, &a);
+    a.x = x; a.idx = const_cast<int32_t *>(topk_idx);
+    a.counts = counts; a.offsets = offsets; a.perm = perm; a.inv_perm = inv_perm; a.x_perm = x_perm;
+    a.status_dev = status_dev;
+    return dispatch_launches(pl, a, false, (hipStream_t)stream);
 }
 
 int moe_megakernel_forward(const moe_problem_t *p, const void *x, const void *Wg, const float *gate_bias,

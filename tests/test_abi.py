@@ -87,7 +87,7 @@ def test_null_pointers_and_zero_epoch(B):
     p = B.problem(256, 512, 8, 2, 1024, 2, "bf16")
     lib = ctypes.CDLL(LIB)
     assert lib.moe_route(ctypes.byref(p), None, None, None, None, None, None) == B.MOE_ERR_INVALID_ARG
-    assert lib.moe_dispatch(ctypes.byref(p), *([None] * 9)) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_dispatch(ctypes.byref(p), *([None] * 10)) == B.MOE_ERR_INVALID_ARG
     assert lib.moe_megakernel_forward(ctypes.byref(p), *([None] * 19)) == B.MOE_ERR_INVALID_ARG
     assert lib.moe_combine(ctypes.byref(p), *([None] * 7)) == B.MOE_ERR_INVALID_ARG
     assert lib.moe_workspace_init(ctypes.byref(p), None, None) == B.MOE_ERR_WORKSPACE

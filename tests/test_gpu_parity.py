@@ -21,15 +21,16 @@ def _dev(inp, names):
     return {n: (inp[n].cuda() if inp.get(n) is not None else None) for n in names}
 
 
-def _problem(B, cfg, signal_mode=1, fence_scope=0, epoch=1, group_size=0, scheduler=0, capacity=0):
+def _problem(B, cfg, signal_mode=1, fence_scope=0, epoch=1, group_size=0, scheduler=0, capacity=0, wait_ticks=0):
     return B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
                      tile_n=cfg["tile_n"], signal_mode=signal_mode, fence_scope=fence_scope, epoch=epoch,
-                     group_size=group_size, scheduler=scheduler, capacity=capacity)
+                     group_size=group_size, scheduler=scheduler, capacity=capacity, wait_ticks=wait_ticks)
 
 
-def run_forward(B, inp, signal_mode, fence_scope, epoch=1, buf=None, group_size=0, scheduler=0, capacity=0):
+def run_forward(B, inp, signal_mode, fence_scope, epoch=1, buf=None, group_size=0, scheduler=0, capacity=0,
+                wait_ticks=0):
     cfg = inp["cfg"]
-    p = _problem(B, cfg, signal_mode, fence_scope, epoch, group_size, scheduler, capacity)
+    p = _problem(B, cfg, signal_mode, fence_scope, epoch, group_size, scheduler, capacity, wait_ticks)
     buf = buf or B.Buffers(p)
     d = _dev(inp, ("x", "Wg", "gate_bias", "W1", "W3", "W2"))
     if cfg["prerouted"] is not None:
@@ -254,7 +255,7 @@ def test_dispatch_parity(name):
     idx = torch.from_numpy(ridx).cuda()
     x_perm = torch.full((cfg["T"] * cfg["k"], cfg["d"]), float("nan"), dtype=x.dtype, device="cuda")
     for rep in range(2):  # twice: the workspace must be reusable
-        B.moe_dispatch(p, x, idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, x_perm, buf.workspace)
+        B.moe_dispatch(p, x, idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, x_perm, None, buf.workspace)
         torch.cuda.synchronize()
         counts, offsets, perm, inv = oracle.dispatch(ridx, cfg["E"])
         assert np.array_equal(buf.counts.cpu().numpy(), counts)
@@ -264,7 +265,7 @@ def test_dispatch_parity(name):
         ref_xp = oracle.gather(W.as_oracle_array(inp["x"]), perm, cfg["k"])
         assert np.array_equal(W.as_oracle_array(x_perm), ref_xp)  # byte-exact row copy
     # indices only
-    B.moe_dispatch(p, None, idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, None, buf.workspace)
+    B.moe_dispatch(p, None, idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, None, None, buf.workspace)
     torch.cuda.synchronize()
     assert np.array_equal(buf.perm.cpu().numpy(), perm)
 
@@ -276,7 +277,7 @@ def test_dispatch_empty_experts():
     p = B.problem(T, d, E, k, 64, 4, "bf16")
     buf = B.Buffers(p)
     ridx = np.tile(np.array([[5, 2]], np.int32), (T, 1))
-    B.moe_dispatch(p, None, torch.from_numpy(ridx).cuda(), buf.counts, buf.offsets, buf.perm, buf.inv_perm, None,
+    B.moe_dispatch(p, None, torch.from_numpy(ridx).cuda(), buf.counts, buf.offsets, buf.perm, buf.inv_perm, None, None,
                    buf.workspace)
     torch.cuda.synchronize()
     counts, offsets, perm, inv = oracle.dispatch(ridx, E)
@@ -332,7 +333,7 @@ def test_dispatch_padded_layout(name):
         p = _problem(B, cfg, capacity=cap)
         buf = B.Buffers(p)
         x_perm = torch.full((cfg["E"] * cap, cfg["d"]), float("nan"), dtype=x.dtype, device="cuda")
-        B.moe_dispatch(p, x, idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, x_perm, buf.workspace)
+        B.moe_dispatch(p, x, idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, x_perm, None, buf.workspace)
         torch.cuda.synchronize()
         counts, offsets, perm, inv = oracle.dispatch(ridx, cfg["E"], capacity=cap)
         assert np.array_equal(buf.counts.cpu().numpy(), counts)
@@ -345,7 +346,7 @@ def test_dispatch_padded_layout(name):
     buf = B.Buffers(p)
     buf.perm.fill_(-7)
     x_perm = torch.full((cfg["E"] * (cmax - 1), cfg["d"]), 3.0, dtype=x.dtype, device="cuda")
-    B.moe_dispatch(p, x, idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, x_perm, buf.workspace)
+    B.moe_dispatch(p, x, idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, x_perm, None, buf.workspace)
     torch.cuda.synchronize()
     assert np.array_equal(buf.counts.cpu().numpy(), counts)
     assert (buf.perm == -7).all().item() and (x_perm == 3.0).all().item()
@@ -361,7 +362,7 @@ def test_dispatch_many_blocks_and_experts():
     g = torch.Generator().manual_seed(77)
     ridx = torch.rand((T, E), generator=g).argsort(dim=1)[:, :k].to(torch.int32).contiguous()
     for rep in range(2):
-        B.moe_dispatch(p, None, ridx.cuda(), buf.counts, buf.offsets, buf.perm, buf.inv_perm, None, buf.workspace)
+        B.moe_dispatch(p, None, ridx.cuda(), buf.counts, buf.offsets, buf.perm, buf.inv_perm, None, None, buf.workspace)
         torch.cuda.synchronize()
         counts, offsets, perm, inv = oracle.dispatch(ridx.numpy(), E)
         assert np.array_equal(buf.counts.cpu().numpy(), counts)
@@ -372,7 +373,7 @@ def test_dispatch_many_blocks_and_experts():
     cap = int(counts.max()) + 1
     p = B.problem(T, d, E, k, 64, 8, "bf16", capacity=cap)
     buf = B.Buffers(p)
-    B.moe_dispatch(p, None, ridx.cuda(), buf.counts, buf.offsets, buf.perm, buf.inv_perm, None, buf.workspace)
+    B.moe_dispatch(p, None, ridx.cuda(), buf.counts, buf.offsets, buf.perm, buf.inv_perm, None, None, buf.workspace)
     torch.cuda.synchronize()
     counts, offsets, perm, inv = oracle.dispatch(ridx.numpy(), E, capacity=cap)
     assert np.array_equal(buf.offsets.cpu().numpy(), offsets)
@@ -388,7 +389,7 @@ def test_dispatch_then_megakernel_share_a_workspace():
     p, buf = run_forward(B, inp, 1, 0, epoch=1)
     ref = check_against_oracle(B, inp, p, buf, 1)
     idx = buf.topk_idx.clone()
-    B.moe_dispatch(p, inp["x"].cuda(), idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, None, buf.workspace)
+    B.moe_dispatch(p, inp["x"].cuda(), idx, buf.counts, buf.offsets, buf.perm, buf.inv_perm, None, None, buf.workspace)
     torch.cuda.synchronize()
     assert np.array_equal(buf.perm.cpu().numpy(), ref["perm"])
     p, buf = run_forward(B, inp, 0, 0, epoch=2, buf=buf)
@@ -450,6 +451,81 @@ def test_bad_routing_is_reported_not_followed():
     good = W.make_inputs("mini_pre")
     p, buf = run_forward(B, good, 1, 0, epoch=2, buf=buf)
     check_against_oracle(B, good, p, buf, 1)
+
+
+def test_dispatch_reports_bad_routing_and_gathers_nothing():
+    """moe_dispatch alone with one expert id outside [0, E): the status says so, counts leave the slot out,
+    and neither perm nor x_perm is written (x_perm keeps its poison), in the short form (block histograms) and
+    in the long one (histograms too large for one workgroup's LDS: the plan form)."""
+    B = _binding()
+    cases = [("short", dict(T=256, d=256, E=8, k=2, f=64, R=4, dtype="bf16", seed=71)),
+             ("long", dict(T=8192, d=64, E=200, k=2, f=64, R=4, dtype="bf16", seed=72))]
+    for form, cfg in cases:
+        print(f"case bad id, {form} form", flush=True)
+        cfg = W.config(cfg)
+        inp = W.make_inputs(cfg, with_weights=False)
+        T, d, E, k = cfg["T"], cfg["d"], cfg["E"], cfg["k"]
+        r = np.random.default_rng(cfg["seed"])
+        ridx = np.stack([r.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+        good = ridx.copy()
+        ridx[T // 3, 1] = E + 5
+        p = _problem(B, cfg)
+        buf = B.Buffers(p)
+        x = inp["x"].cuda()
+        x_perm = torch.full((T * k, d), float("nan"), dtype=x.dtype, device="cuda")
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        buf.perm.fill_(-7)
+        B.moe_dispatch(p, x, torch.from_numpy(ridx).cuda(), buf.counts, buf.offsets, buf.perm, buf.inv_perm, x_perm,
+                       status, buf.workspace)
+        torch.cuda.synchronize()
+        assert int(status.item()) == B.MOE_ERR_BAD_ROUTING, (form, int(status.item()))
+        want = np.bincount(ridx.reshape(-1)[ridx.reshape(-1) < E], minlength=E)
+        assert np.array_equal(buf.counts.cpu().numpy(), want)
+        assert torch.isnan(x_perm).all().item(), "rows were gathered although the routing is invalid"
+        # the same buffers and workspace right after, valid routing: status untouched, result right
+        status.zero_()
+        B.moe_dispatch(p, x, torch.from_numpy(good).cuda(), buf.counts, buf.offsets, buf.perm, buf.inv_perm, x_perm,
+                       status, buf.workspace)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        counts, offsets, perm, inv = oracle.dispatch(good, E)
+        assert np.array_equal(buf.counts.cpu().numpy(), counts) and np.array_equal(buf.perm.cpu().numpy(), perm)
+        assert np.array_equal(buf.inv_perm.cpu().numpy(), inv)
+        xp = oracle.gather(W.as_oracle_array(inp["x"]), perm, k)
+        assert np.array_equal(x_perm.cpu().view(torch.uint16).numpy(), xp)
+    # over capacity (padded layout) is reported the same way
+    cfg = W.config(cases[0][1])
+    p = _problem(B, cfg, capacity=8)
+    buf = B.Buffers(p)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    skew = np.zeros((cfg["T"], cfg["k"]), np.int32)
+    skew[:, 1] = 1
+    B.moe_dispatch(p, None, torch.from_numpy(skew).cuda(), buf.counts, buf.offsets, buf.perm, buf.inv_perm, None, status,
+                   buf.workspace)
+    torch.cuda.synchronize()
+    assert int(status.item()) == B.MOE_ERR_CAPACITY
+
+
+def test_epoch_reuse_needs_zeroed_flags():
+    """Epochs 1, 2, then 1 again with other routing, on one set of buffers: legal only because the flags are zeroed
+    before the value is reused (a flag the second call set and the third does not publish would otherwise still say
+    2, and one the first call set would read as ready).  Every call is checked in full, flags beyond those in use
+    included."""
+    B = _binding()
+    a = W.make_inputs("mini_skew")
+    b = W.make_inputs(dict(W.CONFIGS["mini_skew"], seed=113, bias_std=0.2))
+    p, buf = run_forward(B, a, 1, 0, epoch=1)
+    check_against_oracle(B, a, p, buf, 1)
+    p, buf = run_forward(B, b, 1, 0, epoch=2, buf=buf)
+    check_against_oracle(B, b, p, buf, 1)
+    buf.flags.zero_()
+    p, buf = run_forward(B, a, 0, 0, epoch=1, buf=buf)
+    check_against_oracle(B, a, p, buf, 0)
+    idx, _, _ = parity.oracle_routing(a)
+    _, offsets, _, inv = oracle.dispatch(idx, a["cfg"]["E"])
+    nfl = oracle.publish_plan(idx, offsets, inv, a["cfg"]["E"], a["cfg"]["R"], a["cfg"]["d"], a["cfg"]["tile_m"],
+                              a["cfg"]["tile_n"])["n_flags"]
+    assert not buf.flags[nfl:].any().item(), "a flag outside the tiles of this call was touched"
 
 
 def _random_cases(seed, n):
@@ -544,7 +620,7 @@ def test_standalone_entry_points_random_shapes():
             counts, offsets, perm, inv = oracle.dispatch(ridx, E, capacity=cap)
             for rep in range(2):
                 B.moe_dispatch(pc, dv["x"] if with_x else None, torch.from_numpy(ridx).cuda(), buf.counts, buf.offsets,
-                               buf.perm, buf.inv_perm, x_perm, buf.workspace)
+                               buf.perm, buf.inv_perm, x_perm, None, buf.workspace)
                 torch.cuda.synchronize()
                 assert np.array_equal(buf.counts.cpu().numpy(), counts)
                 assert np.array_equal(buf.offsets.cpu().numpy(), offsets)
@@ -587,22 +663,18 @@ def test_repeat_launches_are_bit_identical(scheduler):
 
 @pytest.mark.parametrize("scheduler", [0, 1])
 def test_expired_waits_drain_the_kernel(scheduler):
-    """The time-out path, forced from the host: with the bound of the in-kernel waits set to one tick, the
-    plan's wait for the gate gives up, the error spreads, every workgroup leaves in the ordinary way and the call
-    reports MOE_ERR_TIMEOUT.  With the bound restored and the workspace initialised again, the same buffers give
-    the right result."""
+    """The time-out path, forced from the host: a call whose bound of the in-kernel waits is one tick
+    (moe_problem_t.wait_ticks; nothing global changes): the plan's wait for the gate gives up, the error spreads,
+    every workgroup leaves in the ordinary way and the call reports MOE_ERR_TIMEOUT.  With the workspace
+    initialised again, the same buffers give the right result in a call with the default bound."""
     B = _binding()
     inp = W.make_inputs("mini_bf16")
     p, buf = run_forward(B, inp, 1, 0, epoch=1, scheduler=scheduler)
     ref = check_against_oracle(B, inp, p, buf, 1)
-    try:
-        B.moe_debug_set_wait_limit(1)
-        print(f"case mini_bf16 scheduler {scheduler}, wait limit 1 tick", flush=True)
-        p, buf = run_forward(B, inp, 1, 0, epoch=2, buf=buf, scheduler=scheduler)
-        stats = buf.stats.cpu().numpy()
-        assert int(stats[7]) == B.MOE_ERR_TIMEOUT and stats[6] > 0, stats.tolist()
-    finally:
-        B.moe_debug_set_wait_limit(0)
+    print(f"case mini_bf16 scheduler {scheduler}, wait limit 1 tick", flush=True)
+    p, buf = run_forward(B, inp, 1, 0, epoch=2, buf=buf, scheduler=scheduler, wait_ticks=1)
+    stats = buf.stats.cpu().numpy()
+    assert int(stats[7]) == B.MOE_ERR_TIMEOUT and stats[6] > 0, stats.tolist()
     B.moe_workspace_init(p, buf.workspace)
     buf.flags.zero_()
     p, buf = run_forward(B, inp, 1, 0, epoch=3, buf=buf, scheduler=scheduler)
