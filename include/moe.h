@@ -194,6 +194,26 @@ int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx,
                  int32_t *status_dev, void *workspace, void *stream);
 
 /*
+ * moe_dispatch for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments (minus the workspace), same results, same
+ * kernels; the one scratch buffer those kernels need (the per-block expert
+ * histograms, ceil(T/64) * E int32) lives in a static array of 64 KB in device
+ * memory that belongs to the library: one copy per GPU the library runs on, held
+ * until the process ends.  The call allocates and frees nothing.
+ *   Limit (the form of the dispatch whose histograms fit one workgroup's LDS):
+ *   4 * (ceil(T/64) * E + 3 * (E + 1)) + 8 * E <= 65536, e.g. T <= 7808 at
+ *   E = 128 and T <= 130688 at E = 8; beyond it MOE_ERR_UNSUPPORTED is returned
+ *   before anything is launched.
+ *   Every call on a GPU uses that GPU's array, which keeps what the last call
+ *   left (each call overwrites the part it reads, nothing has to start at
+ *   zero): calls that overlap in time on one GPU, on whatever streams, race.
+ */
+int moe_dispatch_noalloc(const moe_problem_t *p, const void *x, const int32_t *topk_idx,
+                         int32_t *counts, int32_t *offsets, int32_t *perm, int32_t *inv_perm,
+                         void *x_perm, int32_t *status_dev, void *stream);
+
+/*
  * The whole layer in ONE persistent kernel (sections 2.1, 2.3, 4.1): gate,
  * dispatch, per-expert SwiGLU FFN  y = (silu(x W1[e]) * (x W3[e])) W2[e]
  * as a grouped GEMM, publication of every finished y tile into `staging`

@@ -22,7 +22,7 @@ MOE_SCHED_STATIC, MOE_SCHED_READY_QUEUE = 0, 1
 MOE_NUM_STATS = 20
 
 EXPORTS = ("moe_workspace_bytes", "moe_num_flags", "moe_status_string", "moe_workspace_init", "moe_route",
-           "moe_dispatch", "moe_megakernel_forward", "moe_combine")
+           "moe_dispatch", "moe_dispatch_noalloc", "moe_megakernel_forward", "moe_combine")
 
 
 class MoeProblem(ctypes.Structure):
@@ -53,9 +53,11 @@ _lib.moe_status_string.argtypes = [ctypes.c_int]
 _lib.moe_workspace_init.argtypes = [_pp, _vp, _vp]
 _lib.moe_route.argtypes = [_pp] + [_vp] * 6
 _lib.moe_dispatch.argtypes = [_pp] + [_vp] * 10
+_lib.moe_dispatch_noalloc.argtypes = [_pp] + [_vp] * 9
 _lib.moe_megakernel_forward.argtypes = [_pp] + [_vp] * 19
 _lib.moe_combine.argtypes = [_pp] + [_vp] * 7
-for _n in ("moe_workspace_init", "moe_route", "moe_dispatch", "moe_megakernel_forward", "moe_combine"):
+for _n in ("moe_workspace_init", "moe_route", "moe_dispatch", "moe_dispatch_noalloc", "moe_megakernel_forward",
+           "moe_combine"):
     getattr(_lib, _n).restype = ctypes.c_int
 
 
@@ -111,6 +113,12 @@ def moe_dispatch(p, x, topk_idx, counts, offsets, perm, inv_perm, x_perm, status
     _check(_lib.moe_dispatch(ctypes.byref(p), _ptr(x), _ptr(topk_idx), _ptr(counts), _ptr(offsets), _ptr(perm),
                              _ptr(inv_perm), _ptr(x_perm), _ptr(status_dev), _ptr(workspace), _stream(stream)),
            "moe_dispatch")
+
+
+def moe_dispatch_noalloc(p, x, topk_idx, counts, offsets, perm, inv_perm, x_perm, status_dev, stream=None):
+    _check(_lib.moe_dispatch_noalloc(ctypes.byref(p), _ptr(x), _ptr(topk_idx), _ptr(counts), _ptr(offsets), _ptr(perm),
+                                     _ptr(inv_perm), _ptr(x_perm), _ptr(status_dev), _stream(stream)),
+           "moe_dispatch_noalloc")
 
 
 def moe_megakernel_forward(p, x, Wg, gate_bias, W1, W3, W2, topk_idx, topk_w, counts, offsets, perm, inv_perm,

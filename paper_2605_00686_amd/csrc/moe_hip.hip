@@ -572,6 +572,28 @@ static int launch_mega(const Plan &pl, const KArgs &a_in, hipStream_t st) {
 
 using namespace moe;
 
+// ---- scratch for callers that cannot allocate (see moe_dispatch_noalloc): one array per GPU the library runs on,
+// held until the process ends.  In host code the array's name is only a handle: the device address comes from
+// hipGetSymbolAddress, once per device with that device current, and only that address is handed to kernels.
+constexpr size_t kStaticScratchBytes = 64 * 1024;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static int static_scratch_address(unsigned char **out) {
+    static std::mutex lock;
+    static unsigned char *addr[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return MOE_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> g(lock);
+    if (!addr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return MOE_ERR_HIP;
+        addr[dev] = (unsigned char *)ptr;
+    }
+    *out = addr[dev];
+    return MOE_OK;
+}
+
 extern "C" {
 
 const char *moe_status_string(int s) {
@@ -632,8 +654,9 @@ int moe_route(const moe_problem_t *p, const void *x, const void *Wg, const float
     return hip_ok(hipGetLastError());
 }
 
-// The launches of a dispatch.  `short_only`: the form that needs the control block and the plan's tables is not
-// available (no workspace).
+// The launches of a dispatch, shared by moe_dispatch (scratch in the caller's workspace) and
+// moe_dispatch_noalloc (scratch in this library's static device array).  `short_only`: the form that needs the
+// control block and the plan's tables is not available.
 static int dispatch_launches(const Plan &pl, const KArgs &a, bool short_only, hipStream_t st) {
     const moe_problem_t *p = &pl.p;
     int rc;
@@ -687,6 +710,27 @@ int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx,
     a.counts = counts; a.offsets = offsets; a.perm = perm; a.inv_perm = inv_perm; a.x_perm = x_perm;
     a.status_dev = status_dev;
     return dispatch_launches(pl, a, false, (hipStream_t)stream);
+}
+
+int moe_dispatch_noalloc(const moe_problem_t *p, const void *x, const int32_t *topk_idx, int32_t *counts,
+                         int32_t *offsets, int32_t *perm, int32_t *inv_perm, void *x_perm, int32_t *status_dev,
+                         void *stream) {
+    Plan pl;
+    int rc = make_plan(p, &pl);
+    if (rc) return rc;
+    if (!topk_idx || !counts || !offsets || !perm || !inv_perm) return MOE_ERR_INVALID_ARG;
+    if (x_perm && !x) return MOE_ERR_INVALID_ARG;
+    // the block histograms, the only scratch of the short form, must fit the static array
+    if ((size_t)pl.nPB * p->E * 4 > kStaticScratchBytes) return MOE_ERR_UNSUPPORTED;
+    unsigned char *scratch_dev = nullptr;
+    if ((rc = static_scratch_address(&scratch_dev))) return rc;
+    KArgs a;
+    fill_args(pl, nullptr, &a);  // no workspace: no control block, no plan tables
+    a.blk_base = (int32_t *)scratch_dev;
+    a.x = x; a.idx = const_cast<int32_t *>(topk_idx);
+    a.counts = counts; a.offsets = offsets; a.perm = perm; a.inv_perm = inv_perm; a.x_perm = x_perm;
+    a.status_dev = status_dev;
+    return dispatch_launches(pl, a, true, (hipStream_t)stream);
 }
 
 int moe_megakernel_forward(const moe_problem_t *p, const void *x, const void *Wg, const float *gate_bias,
