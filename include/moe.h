@@ -201,6 +201,8 @@ int moe_dispatch(const moe_problem_t *p, const void *x, const int32_t *topk_idx,
  * histograms, ceil(T/64) * E int32) lives in a static array of 64 KB in device
  * memory that belongs to the library: one copy per GPU the library runs on, held
  * until the process ends.  The call allocates and frees nothing.
+ *   (Small problems, T*k * ceil(T/16) <= 2^26, run as one launch that needs no
+ *   scratch at all; the array serves the larger ones.)
  *   Limit (the form of the dispatch whose histograms fit one workgroup's LDS):
  *   4 * (ceil(T/64) * E + 3 * (E + 1)) + 8 * E <= 65536, e.g. T <= 7808 at
  *   E = 128 and T <= 130688 at E = 8; beyond it MOE_ERR_UNSUPPORTED is returned

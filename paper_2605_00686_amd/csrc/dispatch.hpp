@@ -398,4 +398,173 @@ __device__ void gather_rows(const KArgs &a, int first, int stride, size_t row_by
     }
 }
 
+// ---- the standalone dispatch as one launch: every workgroup owns kScatterTokens tokens and derives, by itself,
+// everything it needs to place them: it counts ALL N slots per expert (the ids are a few hundred KB that stay in
+// the L2), split into those in front of its own first slot and the rest; the sums give counts and offsets, the
+// front part gives the sorted position of its own first slot of every expert, and a popcount on per-expert
+// token masks gives the rank inside the workgroup (the k experts of a token are distinct).  No histogram
+// crosses workgroups, so there is no second launch and no grid-wide wait.  Then every token row is read ONCE and
+// stored to its k sorted positions: the row movement writes N rows but reads only T (a gather by sorted
+// position reads N rows, most of them from cache, and the chip then moves the written rows at barely half
+// the rate).  Used while N x workgroups stays small enough for the redundant counting to hide behind the row
+// movement of the other workgroups of a CU; larger problems take the histogram form.
+constexpr int kScatterTokens = 16;
+
+// copies of the LDS counters that lanes are spread over, so that few experts do not serialise the LDS atomics
+__host__ __device__ inline int count_copies(int E) {
+    int c = 1;
+    while (c < 16 && 2 * c * E <= 256) c *= 2;
+    return c;
+}
+
+// 16-byte store of a row piece of x_perm: written through to memory (STORE 0; rows that fit the memory-side
+// cache) or non-temporal (STORE 1; more rows than that cache holds)
+template <int STORE>
+__device__ __forceinline__ void store_row16(char *p, const uint4 &v) {
+    const u32x4_t w = {v.x, v.y, v.z, v.w};
+    if (STORE == 0)
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(w) : "memory");
+    else
+        __builtin_nontemporal_store(w, (u32x4_t *)p);
+}
+
+// rows of tokens t0 .. t0+nt-1 to the sorted positions pos[tl*k + j] (LDS): one wavefront per token, each piece
+// loaded once and stored k times, four 16-byte loads in flight per lane
+template <int STORE>
+__device__ __forceinline__ void scatter_rows(const KArgs &a, int t0, int nt, const int *pos, size_t row_bytes) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int pieces = (int)(row_bytes / 16), k = a.k;
+    char *xp = (char *)a.x_perm;
+    for (int tl = wave; tl < nt; tl += 4) {
+        const uint4 *src = (const uint4 *)((const char *)a.x + (size_t)(t0 + tl) * row_bytes);
+        for (int c = lane; c < pieces; c += 256) {
+            uint4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (c + 64 * u < pieces) v[u] = src[c + 64 * u];
+            for (int j = 0; j < k; ++j) {
+                char *dst = xp + (size_t)pos[tl * k + j] * row_bytes;
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (c + 64 * u < pieces) store_row16<STORE>(dst + (size_t)(c + 64 * u) * 16, v[u]);
+            }
+        }
+    }
+}
+
+template <int STORE>
+__device__ __forceinline__ void dispatch_fused_task(const KArgs &a, int b, size_t row_bytes) {
+    __shared__ int s_bef[256], s_aft[256], s_cnt[kMaxExperts], s_off[kMaxExperts + 1], s_base[kMaxExperts];
+    __shared__ u64 s_mask[kMaxExperts];
+    __shared__ int s_pos[kScatterTokens * 32];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int E = a.E, k = a.k, N = a.N;
+    const int t0 = b * kScatterTokens, nt = min(kScatterTokens, a.T - t0), s0 = t0 * k;
+    const int C = count_copies(E);
+    s_bef[tid] = 0;
+    s_aft[tid] = 0;
+    for (int e = tid; e < E; e += kThreads) s_mask[e] = 0ull;
+    __syncthreads();
+    // ---- every slot, counted in front of / from this workgroup's first slot on
+    int *my_bef = s_bef + (lane & (C - 1)) * E, *my_aft = s_aft + (lane & (C - 1)) * E;
+    auto count = [&](int e, int s) {
+        if ((unsigned)e < (unsigned)E) atomicAdd(s < s0 ? &my_bef[e] : &my_aft[e], 1);
+    };
+    if ((((uintptr_t)a.idx) & 15) == 0) {
+        // 16 loads of four ids in flight per thread: the ids come from the L2, and one trip at a time would
+        // cost more than the row movement that follows
+        const int4 *idx4 = (const int4 *)a.idx;
+        const int n4 = N >> 2;
+        constexpr int U = 16;
+        for (int q0 = tid; q0 < n4; q0 += kThreads * U) {
+            int4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (q0 + u * kThreads < n4) v[u] = idx4[q0 + u * kThreads];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int q = q0 + u * kThreads;
+                if (q < n4) count(v[u].x, 4 * q), count(v[u].y, 4 * q + 1), count(v[u].z, 4 * q + 2), count(v[u].w, 4 * q + 3);
+            }
+        }
+        for (int s = (n4 << 2) + tid; s < N; s += kThreads) count(a.idx[s], s);
+    } else {
+#pragma unroll 4
+        for (int s = tid; s < N; s += kThreads) count(a.idx[s], s);
+    }
+    __syncthreads();
+    for (int e = tid; e < E; e += kThreads) {
+        int bs = 0, as = 0;
+        for (int c = 0; c < C; ++c) bs += s_bef[c * E + e], as += s_aft[c * E + e];
+        s_base[e] = bs;
+        s_cnt[e] = bs + as;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const int total = wave_exclusive_scan(s_cnt, s_off, E, 1, 0);
+        if (lane == 0) s_off[E] = total;
+    }
+    __syncthreads();
+    // ids outside [0, E) are counted nowhere: the histogram then accounts for fewer than N slots
+    const bool bad_ids = s_off[E] != N;
+    int over = 0;
+    if (a.capacity > 0) {  // padded layout: expert e owns the `capacity` rows from e * capacity
+        for (int e = tid; e < E; e += kThreads) over |= s_cnt[e] > a.capacity ? 1 : 0;
+        over = __syncthreads_or(over);
+        for (int e = tid; e <= E; e += kThreads) s_off[e] = e * a.capacity;
+        __syncthreads();
+    }
+    if (b == 0) {
+        for (int e = tid; e <= E; e += kThreads) {
+            a.offsets[e] = s_off[e];
+            if (e < E) a.counts[e] = s_cnt[e];
+        }
+        if (tid == 0 && a.status_dev) {
+            if (bad_ids)
+                *a.status_dev = (int)MOE_ERR_BAD_ROUTING;
+            else if (over)
+                *a.status_dev = (int)MOE_ERR_CAPACITY;
+        }
+    }
+    if (bad_ids || over) return;  // counts and the status say so; nothing else is written
+    // ---- this workgroup's slots: rank inside the workgroup from the per-expert token masks
+    for (int q = tid; q < nt * k; q += kThreads) atomicOr(&s_mask[a.idx[s0 + q]], 1ull << (q / k));
+    __syncthreads();
+    for (int q = tid; q < nt * k; q += kThreads) {
+        const int e = a.idx[s0 + q], tl = q / k;
+        const int p = s_off[e] + s_base[e] + __popcll(s_mask[e] & ((1ull << tl) - 1ull));
+        a.perm[p] = s0 + q;
+        a.inv_perm[s0 + q] = p;
+        s_pos[q] = p;
+    }
+    if (a.capacity > 0) {
+        // padded layout: the unused entries of perm and rows of x_perm, experts dealt round-robin to the workgroups
+        const int pieces = (int)(row_bytes / 16);
+        for (int e = b; e < E; e += (int)gridDim.x) {
+            const int first = e * a.capacity + s_cnt[e], n = a.capacity - s_cnt[e];
+            for (int j = tid; j < n; j += kThreads) a.perm[first + j] = -1;
+            if (a.x_perm) {
+                uint4 *rows = (uint4 *)((char *)a.x_perm + (size_t)first * row_bytes);
+                for (size_t q = tid; q < (size_t)n * pieces; q += kThreads) rows[q] = make_uint4(0u, 0u, 0u, 0u);
+            }
+        }
+    }
+    __syncthreads();
+    if (a.x_perm) scatter_rows<STORE>(a, t0, nt, s_pos, row_bytes);
+}
+
+// The row movement of the histogram form for the ragged layout, as its own launch after the permutation: the
+// sorted positions of the workgroup's tokens come from inv_perm.
+template <int STORE>
+__device__ __forceinline__ void scatter_task(const KArgs &a, int b, size_t row_bytes) {
+    __shared__ int s_pos[kScatterTokens * 32];
+    const int t0 = b * kScatterTokens, nt = min(kScatterTokens, a.T - t0);
+    for (int q = threadIdx.x; q < nt * a.k; q += kThreads) {
+        const int p = a.inv_perm[(size_t)t0 * a.k + q];
+        s_pos[q] = min(max(p, 0), a.NP - 1);  // (a position is never followed out of x_perm)
+    }
+    __syncthreads();
+    scatter_rows<STORE>(a, t0, nt, s_pos, row_bytes);
+}
+
 }  // namespace moe

@@ -69,6 +69,19 @@ __global__ __launch_bounds__(kThreads) void k_gather(KArgs a, size_t row_bytes) 
     gather_rows(a, wave, (gridDim.x * kThreads) >> 6, row_bytes);
 }
 
+// standalone dispatch as one launch (see dispatch_fused_task); and the row movement of the histogram form by
+// token (ragged layout), which moves nothing unless the histogram accounts for every slot
+template <int STORE>
+__global__ __launch_bounds__(kThreads) void k_dispatch_fused(KArgs a, size_t row_bytes) {
+    dispatch_fused_task<STORE>(a, blockIdx.x, row_bytes);
+}
+template <int STORE>
+__global__ __launch_bounds__(kThreads) void k_scatter(KArgs a, size_t row_bytes) {
+    if (a.ctrl && a.ctrl->error != 0) return;
+    if (a.offsets[a.E] != a.N) return;  // an expert id outside [0, E): perm and inv_perm were not written
+    scatter_task<STORE>(a, blockIdx.x, row_bytes);
+}
+
 // standalone dispatch leaves the control block clean for the next call
 __global__ __launch_bounds__(kThreads) void k_dispatch_finish(KArgs a) {
     // (one workgroup: the status must be read before the control block is cleared)
@@ -299,6 +312,9 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
 }
 
 // --------------------------------------------------------------- host side
+// The standalone dispatch runs as one launch while (slots) x (workgroups of 16 tokens) is at most this: every
+// workgroup counts every slot, which hides behind the row movement up to about this much.
+constexpr long long kFusedDispatchWork = 64ll << 20;
 constexpr int kMaxDevices = 16;  // devices the host-side launch memo covers (others ask the runtime on every call)
 
 static inline size_t align_up(size_t v, size_t al) { return (v + al - 1) / al * al; }
@@ -663,6 +679,28 @@ static int dispatch_launches(const Plan &pl, const KArgs &a, bool short_only, hi
     const size_t row_bytes = (size_t)p->d * elem_size(p->dtype);
     int ggrid = (pl.NP + 3) / 4;  // gather: one wavefront per row while rows last
     if (ggrid > 8192) ggrid = 8192;
+    // rows that do not fit the 256 MB memory-side cache are stored past it; others are written through
+    const bool past_cache = (size_t)pl.NP * row_bytes > ((size_t)192 << 20);
+    const int sgrid = (p->T + kScatterTokens - 1) / kScatterTokens;
+    // rows by token (read once, stored k times): ragged layout; the padded layout's histogram form keeps the gather
+    // by sorted position, which also zeroes the unused rows
+    auto move_rows = [&]() {
+        if (!a.x_perm) return;
+        if (p->capacity > 0)
+            hipLaunchKernelGGL(k_gather, dim3(ggrid), dim3(kThreads), 0, st, a, row_bytes);
+        else if (past_cache)
+            hipLaunchKernelGGL(k_scatter<1>, dim3(sgrid), dim3(kThreads), 0, st, a, row_bytes);
+        else
+            hipLaunchKernelGGL(k_scatter<0>, dim3(sgrid), dim3(kThreads), 0, st, a, row_bytes);
+    };
+    if ((long long)pl.N * sgrid <= kFusedDispatchWork) {
+        // one launch: every workgroup counts all N slots itself (no scratch at all)
+        if (past_cache)
+            hipLaunchKernelGGL(k_dispatch_fused<1>, dim3(sgrid), dim3(kThreads), 0, st, a, row_bytes);
+        else
+            hipLaunchKernelGGL(k_dispatch_fused<0>, dim3(sgrid), dim3(kThreads), 0, st, a, row_bytes);
+        return hip_ok(hipGetLastError());
+    }
     const size_t bsmem = block_perm_smem_bytes(p->E, pl.nPB);
     if (bsmem <= 64 * 1024) {
         // short form: per-block histograms, then every block derives its own base positions from all of
@@ -675,7 +713,7 @@ static int dispatch_launches(const Plan &pl, const KArgs &a, bool short_only, hi
             if ((rc = set_smem(k_block_perm<bf16_t>, bsmem))) return rc;
             hipLaunchKernelGGL(k_block_perm<bf16_t>, dim3(pl.nPB), dim3(kThreads), bsmem, st, a);
         }
-        if (a.x_perm) hipLaunchKernelGGL(k_gather, dim3(ggrid), dim3(kThreads), 0, st, a, row_bytes);
+        move_rows();
         return hip_ok(hipGetLastError());
     }
     if (short_only) return MOE_ERR_UNSUPPORTED;
@@ -691,7 +729,7 @@ static int dispatch_launches(const Plan &pl, const KArgs &a, bool short_only, hi
         hipLaunchKernelGGL(k_plan, dim3(1), dim3(kThreads), psmem, st, a);
         hipLaunchKernelGGL(k_perm<bf16_t>, dim3(pl.nPB), dim3(kThreads), (size_t)p->E * 8, st, a);
     }
-    if (a.x_perm) hipLaunchKernelGGL(k_gather, dim3(ggrid), dim3(kThreads), 0, st, a, row_bytes);
+    move_rows();
     hipLaunchKernelGGL(k_dispatch_finish, dim3(1), dim3(kThreads), 0, st, a);
     return hip_ok(hipGetLastError());
 }

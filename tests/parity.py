@@ -15,8 +15,13 @@ permutation, flag numbering and fence counts bit-exact.  bf16 outputs:
       puts an error of about 1.5e-3 rms(y) on every y; an element then misses a
       2% RELATIVE bound whenever |r| < 0.07 rms(y), i.e. for about 5% of
       Gaussian-distributed outputs, whatever the kernel does.
- (iii) against the bf16-faithful oracle the row-normalised error is at most two
-      bf16 ulps of the row maximum (8e-3).
+ (iii) against the bf16-faithful oracle, per row, in units of the spacing of
+      bf16 numbers (8 significant bits: ulp(v) = 2^(floor(log2 |v|) - 7), between
+      2^-8 and 2^-7 of v): a row of staging may differ by one flipped rounding,
+      max_n |g - r| <= 1.25 ulp(max_n |r|) (the quarter ulp covers what fp32
+      accumulation and flipped roundings of h move the sum before it is rounded);
+      a row of out by what its k staging rows may differ, weighted, plus one
+      flipped rounding of its own: sum_j w_j 1.25 ulp(max |staging_j|) + ulp(max |out|).
 fp32 problems: row-normalised 1e-4.
 """
 from __future__ import annotations
@@ -28,8 +33,31 @@ from paper_2605_00686_amd import workloads as W
 
 REL, ABS_FLOOR = 2e-2, 1e-3
 RATE_FAITHFUL, RATE_EXACT = 1e-3, 0.08
+# Against the EXACT oracle the elementwise rate is bounded per full-size workload by what an ideal bf16 pipeline
+# gives there (measured on the committed seeds) plus one point; RATE_EXACT is the bound for everything else.
+RATE_EXACT_BY_WORKLOAD = {"cfg1": 0.01, "cfg2": 0.0142, "cfg3": 0.0593, "cfg4": 0.0678, "cfg5": 0.0633, "cfg6": 0.0479,
+                          "cfg7": 0.0635, "cfg8": 0.0143}
 REL_F32 = 1e-4
-FAITHFUL_REL = 8e-3  # two bf16 ulps of the row maximum (2 * 2^-8)
+FAITHFUL_REL = 8e-3  # rows without a per-row bound (see faithful_bounds): two bf16 ulps of a row maximum near 2^n
+STAGING_ULPS = 1.25  # one flipped rounding, plus what moves the sum before it is rounded
+
+
+def bf16_ulp(v):
+    """spacing of bf16 numbers around |v| (8 significant bits): 2^(floor(log2 |v|) - 7); 0 where v == 0"""
+    v = np.abs(np.asarray(v, np.float64))
+    out = np.zeros_like(v)
+    nz = v > 0
+    out[nz] = np.exp2(np.floor(np.log2(v[nz])) - 7.0)
+    return out
+
+
+def faithful_bounds(st_f, out_f, w):
+    """Per-row absolute bounds on |GPU - bf16-faithful oracle|: (staging rows [T*k], out rows [T]); st_f is the
+    faithful staging [T*k, d] of the same tokens in slot order, w their gate weights [T, k]."""
+    T, k = w.shape
+    st_b = STAGING_ULPS * bf16_ulp(np.abs(st_f).max(axis=1))
+    out_b = (w.astype(np.float64) * st_b.reshape(T, k)).sum(axis=1) + bf16_ulp(np.abs(out_f).max(axis=1))
+    return st_b, out_b
 
 
 def oracle_arrays(inp):
@@ -58,18 +86,26 @@ def violation_rate(got, ref, rel=REL):
     return float(bad.mean())
 
 
-def check_outputs(name, got, ref, ref_faithful, is_f32):
+def check_outputs(name, got, ref, ref_faithful, is_f32, rate_exact=None, row_bound=None):
     """-> dict of metrics; raises AssertionError with the numbers when a bar fails."""
     m = {"row_err": float(row_err(got, ref).max()), "viol_rate": violation_rate(got, ref)}
     if is_f32:
         assert m["row_err"] <= REL_F32, f"{name}: fp32 row error {m['row_err']:.3e}"
         return m
     assert m["row_err"] <= REL, f"{name}: row-normalised error {m['row_err']:.3e} > {REL}"
-    assert m["viol_rate"] < RATE_EXACT, f"{name}: {m['viol_rate']:.4%} of elements outside tolerance (exact oracle)"
+    bound = RATE_EXACT if rate_exact is None else rate_exact
+    assert m["viol_rate"] < bound, f"{name}: {m['viol_rate']:.4%} of elements outside tolerance (exact oracle, bound {bound})"
     if ref_faithful is not None:
         m["row_err_faithful"] = float(row_err(got, ref_faithful).max())
         m["viol_rate_faithful"] = violation_rate(got, ref_faithful)
-        assert m["row_err_faithful"] <= FAITHFUL_REL, f"{name}: vs bf16-faithful oracle {m['row_err_faithful']:.3e}"
+        if row_bound is None:
+            assert m["row_err_faithful"] <= FAITHFUL_REL, f"{name}: vs bf16-faithful oracle {m['row_err_faithful']:.3e}"
+        else:
+            err = np.abs(got.astype(np.float64) - ref_faithful.astype(np.float64)).max(axis=1)
+            ratio = np.where(row_bound > 0, err / np.where(row_bound > 0, row_bound, 1.0), np.where(err > 0, np.inf, 0.0))
+            m["row_bound_ratio_faithful"] = float(ratio.max())
+            assert m["row_bound_ratio_faithful"] <= 1.0, \
+                f"{name}: row {int(ratio.argmax())} is {m['row_bound_ratio_faithful']:.3f} x its bound against the bf16-faithful oracle"
         assert m["viol_rate_faithful"] < RATE_FAITHFUL, \
             f"{name}: {m['viol_rate_faithful']:.4%} of elements outside tolerance (bf16-faithful oracle)"
     return m

@@ -1,8 +1,12 @@
-"""GPU parity at the full sizes of the five workloads, in the launch
-configuration bench.py times.  Integer results (routing, histogram, permutation,
-flag numbering, fence counts) are compared in full; floating-point outputs are
-compared on sampled tokens the oracle computes one by one (all tokens for the
-fp32 toy layer)."""
+"""GPU parity at the full sizes of the workloads, in the launch configuration
+bench.py times.  Integer results (routing, histogram, permutation, flag
+numbering, fence counts) are compared in full.  Floating-point outputs: EVERY
+row of staging and out for cfg1, cfg2, cfg3, cfg5, cfg6 and cfg8 (the oracle
+runs those layers whole in seconds); for cfg4 and cfg7, whose layers take the
+oracle minutes, the tokens are chosen so that every run of 128 consecutive rows
+of every expert (the compute row blocks are 128 or 256 rows high and start at
+the expert's first row) has its first and its last row checked, across all
+columns: no GEMM tile goes unchecked."""
 import numpy as np
 import pytest
 import torch
@@ -13,7 +17,20 @@ from tests import parity
 
 pytestmark = pytest.mark.gpu
 
-SAMPLES = {"cfg1": 256, "cfg2": 48, "cfg3": 48, "cfg4": 12, "cfg5": 24, "cfg6": 24, "cfg7": 8}
+WHOLE = ("cfg1", "cfg2", "cfg3", "cfg5", "cfg6", "cfg8")  # every token; the others: block-covering tokens
+COVER_ROWS = 128
+
+
+def _tokens(name, cfg, counts, offsets, perm):
+    if name in WHOLE:
+        return np.arange(cfg["T"], dtype=np.int32)
+    rows = set()
+    for e in range(cfg["E"]):
+        for r0 in range(0, int(counts[e]), COVER_ROWS):
+            rows.add(int(offsets[e]) + r0)
+            rows.add(int(offsets[e]) + min(r0 + COVER_ROWS, int(counts[e])) - 1)
+    tok = {int(perm[p]) // cfg["k"] for p in rows} | {0, cfg["T"] - 1}
+    return np.array(sorted(tok), dtype=np.int32)
 
 
 def _run(name, signal_mode, fence_scope, inp=None, buf=None, epoch=1, group_size=0, scheduler=0, capacity=0):
@@ -45,7 +62,8 @@ def _check(B, inp, p, buf, signal_mode, name, cache):
         idx, w, margin = parity.oracle_routing(inp)
         counts, offsets, perm, inv = oracle.dispatch(idx, cfg["E"])
         plan = oracle.publish_plan(idx, offsets, inv, cfg["E"], cfg["R"], cfg["d"], cfg["tile_m"], cfg["tile_n"])
-        tok = W.sample_tokens(cfg, SAMPLES[name])
+        tok = _tokens(name, cfg, counts, offsets, perm)
+        print(f"{name}: oracle on {tok.size} of {cfg['T']} tokens", flush=True)
         st, out = oracle.forward_tokens(o["x"], o["W1"], o["W3"], o["W2"], idx, w, tok)
         stf = outf = None
         if cfg["dtype"] != "f32":
@@ -78,12 +96,16 @@ def _check(B, inp, p, buf, signal_mode, name, cache):
     rows = (tok[:, None] * k + torch.arange(k, device="cuda")[None, :]).reshape(-1)
     got_st = buf.staging[rows].float().cpu().numpy()
     is_f32 = cfg["dtype"] == "f32"
-    m1 = parity.check_outputs("staging", got_st, r["st"], r["stf"], is_f32)
-    m2 = parity.check_outputs("out", got_out, r["out"], r["outf"], is_f32)
+    st_b = out_b = None
+    if not is_f32:
+        st_b, out_b = parity.faithful_bounds(r["stf"], r["outf"], r["w"][r["tok"]])
+    rate = parity.RATE_EXACT_BY_WORKLOAD.get(name)
+    m1 = parity.check_outputs("staging", got_st, r["st"], r["stf"], is_f32, rate_exact=rate, row_bound=st_b)
+    m2 = parity.check_outputs("out", got_out, r["out"], r["outf"], is_f32, rate_exact=rate, row_bound=out_b)
     print(f"{name} mode {signal_mode}: min margin {mm} staging {m1} out {m2} stats {stats.tolist()}", flush=True)
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg5", "cfg6", "cfg4"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg5", "cfg6", "cfg8", "cfg4"])
 def test_fullsize_parity(name):
     print(f"case full-size {name}", flush=True)
     cache = {}
@@ -92,7 +114,7 @@ def test_fullsize_parity(name):
     # the coupled mode on the same buffers (workspace reuse at full size)
     B, inp, p, buf = _run(name, 0, 0, inp=inp, buf=buf, epoch=2)
     _check(B, inp, p, buf, 0, name, cache)
-    if name == "cfg5":  # signaling stress: both scopes as well, and fence groups of 16 flags
+    if name in ("cfg5", "cfg8"):  # signaling stress: both scopes as well, and fence groups of 16 flags
         for epoch, (mode, scope) in enumerate([(1, 1), (0, 1)], start=3):
             B, inp, p, buf = _run(name, mode, scope, inp=inp, buf=buf, epoch=epoch)
             _check(B, inp, p, buf, mode, name, cache)
@@ -122,6 +144,6 @@ def test_fullsize_weights_beyond_2g_elements():
     B, inp, p, buf = _run(name, 1, 0, inp=inp)
     _check(B, inp, p, buf, 1, name, cache)
     hot = np.unique(cache["ref"]["idx"][cache["ref"]["tok"]])
-    assert hot.max() >= 147, "no sampled token reaches an expert whose weights start beyond 2^31 elements"
+    assert hot.max() >= 147, "no checked token reaches an expert whose weights start beyond 2^31 elements"
     B, inp, p, buf = _run(name, 1, 0, inp=inp, buf=buf, epoch=2, scheduler=1)
     _check(B, inp, p, buf, 1, name, cache)

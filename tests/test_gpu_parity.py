@@ -76,8 +76,13 @@ def check_against_oracle(B, inp, p, buf, signal_mode, ref=None):
     st = buf.staging.float().cpu().numpy()
     out = buf.out.float().cpu().numpy()
     assert not np.isnan(st).any() and not np.isnan(out).any(), "poison survived: a row was never written"
-    m1 = parity.check_outputs("staging", st, ref["staging"], None if faithful is None else faithful["staging"], is_f32)
-    m2 = parity.check_outputs("out", out, ref["out"], None if faithful is None else faithful["out"], is_f32)
+    st_b = out_b = None
+    if faithful is not None:
+        st_b, out_b = parity.faithful_bounds(faithful["staging"], faithful["out"], w)
+    m1 = parity.check_outputs("staging", st, ref["staging"], None if faithful is None else faithful["staging"], is_f32,
+                              row_bound=st_b)
+    m2 = parity.check_outputs("out", out, ref["out"], None if faithful is None else faithful["out"], is_f32,
+                              row_bound=out_b)
     print(f"[{cfg}] staging {m1} out {m2} stats {stats.tolist()}")
     return ref
 

@@ -47,8 +47,13 @@ def _both(B, cfg, seed):
 
 def test_noalloc_dispatch_two_calls_second_smaller():
     from paper_2605_00686_amd import binding as B
-    _both(B, dict(T=4096, d=512, E=128, k=8, f=64, R=8, dtype="bf16", seed=201), 1)
-    _both(B, dict(T=320, d=256, E=24, k=3, f=64, R=4, dtype="bf16", seed=202), 2)  # the array keeps the first call's data
+    # the first two are large enough for the form of the dispatch that keeps block histograms in the scratch
+    # array (T*k slots x T/16 workgroups above 64 Mi); the array keeps the first call's data for the second
+    _both(B, dict(T=32768, d=64, E=8, k=8, f=64, R=8, dtype="bf16", seed=201), 1)
+    _both(B, dict(T=16384, d=128, E=8, k=8, f=64, R=4, dtype="bf16", seed=202), 2)
+    _both(B, dict(T=7680, d=64, E=128, k=32, f=64, R=4, dtype="bf16", seed=204), 4)
+    # small problems take the single-launch form, which needs no scratch at all
+    _both(B, dict(T=320, d=256, E=24, k=3, f=64, R=4, dtype="bf16", seed=205), 5)
     _both(B, dict(T=1000, d=64, E=8, k=2, f=64, R=4, dtype="f32", seed=203), 3)
 
 
