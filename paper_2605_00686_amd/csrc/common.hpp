@@ -267,6 +267,16 @@ __device__ __forceinline__ char *lds_at(u32 byte_offset) {
 __device__ __forceinline__ u32 lds_offset(const void *p) {
     return (u32)(uintptr_t)(const __attribute__((address_space(3))) void *)p;
 }
+// The LDS offset of the kernel's dynamic LDS as a plain number in a scalar register, for handing to device
+// functions that are real calls.  Without the empty asm the compiler sees that every caller passes the address
+// of the same LDS variable, moves that variable into the callee, and (a non-kernel function cannot know where a
+// kernel's dynamic LDS starts) looks its offset up in a table in memory: one scalar load plus a wait for ALL
+// outstanding LDS traffic at every use, the GEMM main loop's stage switch included.
+__device__ __forceinline__ u32 lds_offset_opaque(const void *p) {
+    u32 v = (u32)__builtin_amdgcn_readfirstlane((int)lds_offset(p));
+    asm volatile("" : "+s"(v));
+    return v;
+}
 // The argument block of the running kernel sits in constant memory that scalar
 // loads can read.  A kernel whose single parameter is a KArgs takes its address
 // with kernel_args_address() (the compiler only knows it inside the kernel

@@ -837,7 +837,7 @@ __device__ __forceinline__ void ready_queue_stage(const KArgs &a, KArgsAddr karg
     const int tid = threadIdx.x;
     Ctrl *c = a.ctrl;
     StageLds *sl = (StageLds *)(smem + a.sched_lds_off);
-    const u32 lds = lds_offset(smem);
+    const u32 lds = lds_offset_opaque(smem);
     const u64 t0 = kernel_start_ticks(c);
     int q = home, hops = 0;  // the queue tickets come from; hops == kTileQueues: all queues are used up
     int ticket = -1;         // entry of queue q this workgroup is to run (may lie beyond the queue's size), -1 = none

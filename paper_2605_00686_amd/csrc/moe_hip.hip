@@ -252,7 +252,7 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
     if (!bad) {
         // ---- stage 2: GEMM tiles, one call per kind, this XCD's lists first
         const int home = xcd_id() % kTileQueues;
-        const u32 lds = lds_offset(smem);
+        const u32 lds = lds_offset_opaque(smem);
         // The stage functions get the address of a local of this kernel.  That keeps the compiler from
         // marking the calls as tail calls, which is what lets it drop the saving and restoring of
         // callee-saved registers in these functions (they have one caller, which keeps nothing in them):
