@@ -131,6 +131,48 @@ def standalone_ops(B, torch, p, buf, dev, cfg, steps):
     return out
 
 
+def mfma_ceiling(B, torch):
+    """What the matrix cores of THIS box deliver, for holding the grouped GEMM's fraction of the published peak
+    against: (a) the library's probe kernel, nothing but independent bf16 MFMAs at one wavefront per SIMD, on
+    all-zero operands and on operands with the workloads' value distributions (x ~ N(0,1), W ~ N(0,0.02)): the
+    clock the chip holds under matrix-core load depends on its power limit and on the operand bits; (b) the
+    vendor library's GEMM (torch.matmul) on one cfg4 expert's two products with the same distributions."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.empty(cus * 256, dtype=torch.float32, device="cuda")
+    gen = torch.Generator(device="cpu").manual_seed(99)
+    gauss = torch.cat([torch.randn(2048, generator=gen), torch.randn(2048, generator=gen) * 0.02]).to(torch.bfloat16).cuda()
+    iters = 40000  # x 16 products of 32 cycles each: about 14 ms at 1.5 GHz
+
+    def timed(fn, reps):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for e0, e1 in evs:
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        return sum(e0.elapsed_time(e1) for e0, e1 in evs) / reps
+
+    out = {"peak_tflops": MFMA_BF16_PEAK_TF, "compute_units": cus}
+    for label, frag in (("probe_zero_operands", torch.zeros(4096, dtype=torch.bfloat16, device="cuda")),
+                        ("probe_gaussian_operands", gauss)):
+        ms = timed(lambda: B.moe_probe_mfma(frag, iters, cus, sink), 20)
+        tf = cus * 4 * iters * 16 * 32768 / (ms * 1e-3) / 1e12
+        out[label] = {"ms": ms, "tflops": tf, "frac_of_peak": tf / MFMA_BF16_PEAK_TF}
+    T, d, f = 4096, 4096, 14336  # rows of one cfg4 expert, model and FFN dims
+    x = torch.randn(T, d, generator=gen).to(torch.bfloat16).cuda()
+    w1 = (torch.randn(d, f, generator=gen) * 0.02).to(torch.bfloat16).cuda()
+    h = (torch.randn(T, f, generator=gen) * 0.3).to(torch.bfloat16).cuda()
+    w2 = (torch.randn(f, d, generator=gen) * 0.02).to(torch.bfloat16).cuda()
+    for label, (a, b) in (("vendor_gemm_x_w1", (x, w1)), ("vendor_gemm_h_w2", (h, w2))):
+        ms = timed(lambda: torch.matmul(a, b), 20)
+        tf = 2.0 * T * d * f / (ms * 1e-3) / 1e12
+        out[label] = {"ms": ms, "tflops": tf, "frac_of_peak": tf / MFMA_BF16_PEAK_TF, "shape": list(a.shape) + [b.shape[1]]}
+    return out
+
+
 def run_workload(name, args, B, torch, W, steps, warmup, with_cpu, with_ops, calibrate=False):
     """Time `steps` launches of the megakernel on workload `name`; -> dict of everything measured."""
     cfg = W.config(name)
@@ -254,6 +296,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic) so that hardware byte "
                          "counters collected around this command can be scaled")
+    ap.add_argument("--mfma-ceiling", action="store_true",
+                    help="also measure what this box's matrix cores deliver with no memory traffic (the library's "
+                         "probe kernel) and what the vendor GEMM reaches on one cfg4 expert's shapes ('mfma_ceiling')")
     ap.add_argument("--ops", action="store_true",
                     help="also time the standalone entry points (moe_route, moe_dispatch, moe_combine) on the same "
                          "workload and add them to the JSON line as 'standalone_ops'")
@@ -287,6 +332,8 @@ def main():
         sec = run_workload(SECONDARY_WORKLOAD, args, B, torch, W, max(args.steps, 20), max(args.warmup, 5), False, args.ops)
         res["hbm_workload"] = {k: sec[k] for k in ("workload", "tokens_per_s", "ms_per_step", "roofline", "other_roofline",
                                                    "signaling", "timeline_us", "standalone_ops") if k in sec}
+    if args.mfma_ceiling:
+        res["mfma_ceiling"] = mfma_ceiling(B, torch)
     if "cpu_baseline" in main_res:
         res["cpu_baseline"] = main_res["cpu_baseline"]
     print(json.dumps(res))

@@ -253,6 +253,17 @@ int moe_combine(const moe_problem_t *p, const void *staging, const uint32_t *fla
                 const int32_t *slot_flag, const float *topk_w, void *out, int32_t *status_dev,
                 void *stream);
 
+/*
+ * Measurement aid, no part of the layer: the rate at which this GPU's matrix cores retire bf16 work when nothing
+ * else happens (what the grouped GEMM's "fraction of the MFMA peak" can be held against on a given box; the clock
+ * a chip holds under matrix-core load depends on its power limit and on the operand bits).  `workgroups` workgroups
+ * of 4 wavefronts each run `iters` rounds of 16 independent 32x32x16 bf16 products (16 * 32768 FLOP per wavefront
+ * and round) on operands read once from `frag` (device, 8192 bytes: 8 fragments of 16 bytes per lane; any bf16
+ * patterns) and write one float per thread to `sink` (device, workgroups * 256 floats) so that the work is kept.
+ * Asynchronous on `stream`; the caller times it.  FLOPs = workgroups * 4 * iters * 16 * 32768.
+ */
+int moe_probe_mfma(const void *frag, int32_t iters, int32_t workgroups, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

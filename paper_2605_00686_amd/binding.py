@@ -22,7 +22,7 @@ MOE_SCHED_STATIC, MOE_SCHED_READY_QUEUE = 0, 1
 MOE_NUM_STATS = 20
 
 EXPORTS = ("moe_workspace_bytes", "moe_num_flags", "moe_status_string", "moe_workspace_init", "moe_route",
-           "moe_dispatch", "moe_dispatch_noalloc", "moe_megakernel_forward", "moe_combine")
+           "moe_dispatch", "moe_dispatch_noalloc", "moe_megakernel_forward", "moe_combine", "moe_probe_mfma")
 
 
 class MoeProblem(ctypes.Structure):
@@ -56,8 +56,9 @@ _lib.moe_dispatch.argtypes = [_pp] + [_vp] * 10
 _lib.moe_dispatch_noalloc.argtypes = [_pp] + [_vp] * 9
 _lib.moe_megakernel_forward.argtypes = [_pp] + [_vp] * 19
 _lib.moe_combine.argtypes = [_pp] + [_vp] * 7
+_lib.moe_probe_mfma.argtypes = [_vp, ctypes.c_int32, ctypes.c_int32, _vp, _vp]
 for _n in ("moe_workspace_init", "moe_route", "moe_dispatch", "moe_dispatch_noalloc", "moe_megakernel_forward",
-           "moe_combine"):
+           "moe_combine", "moe_probe_mfma"):
     getattr(_lib, _n).restype = ctypes.c_int
 
 
@@ -133,6 +134,10 @@ def moe_megakernel_forward(p, x, Wg, gate_bias, W1, W3, W2, topk_idx, topk_w, co
 def moe_combine(p, staging, flags, slot_flag, topk_w, out, status_dev, stream=None):
     _check(_lib.moe_combine(ctypes.byref(p), _ptr(staging), _ptr(flags), _ptr(slot_flag), _ptr(topk_w), _ptr(out),
                             _ptr(status_dev), _stream(stream)), "moe_combine")
+
+
+def moe_probe_mfma(frag, iters, workgroups, sink, stream=None):
+    _check(_lib.moe_probe_mfma(_ptr(frag), int(iters), int(workgroups), _ptr(sink), _stream(stream)), "moe_probe_mfma")
 
 
 class Buffers:

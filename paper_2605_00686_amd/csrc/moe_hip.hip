@@ -69,6 +69,41 @@ __global__ __launch_bounds__(kThreads) void k_gather(KArgs a, size_t row_bytes) 
     gather_rows(a, wave, (gridDim.x * kThreads) >> 6, row_bytes);
 }
 
+// Measurement aid (moe_probe_mfma): nothing but independent bf16 matrix-core instructions, one wavefront per SIMD,
+// the 256 accumulator registers of the 256 x 256 GEMM tile (16 independent 32x32x16 products per round), operands
+// read once from `frag` (128 bytes per lane of a wavefront, whatever the caller put there).  What this reaches is what
+// the matrix cores deliver on this chip at the clock it holds under that load, with no LDS or memory traffic at all.
+__global__ __launch_bounds__(kThreads, 1) void k_probe_mfma(const uint4 *frag, int iters, float *sink) {
+    const int lane = threadIdx.x & 63;
+    bf16x8_t fa[4], fb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        fa[i] = __builtin_bit_cast(bf16x8_t, frag[(size_t)(i * 64 + lane)]);
+        fb[i] = __builtin_bit_cast(bf16x8_t, frag[(size_t)((4 + i) * 64 + lane)]);
+    }
+    f32x16_t acc[4][4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[m][n][v] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+            for (int n = 0; n < 4; ++n) acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[n], fa[m], acc[m][n], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s += acc[m][n][v];
+    sink[(size_t)blockIdx.x * kThreads + threadIdx.x] = s;
+}
+
 // standalone dispatch as one launch (see dispatch_fused_task); and the row movement of the histogram form by
 // token (ragged layout), which moves nothing unless the histogram accounts for every slot
 template <int STORE>
@@ -819,6 +854,12 @@ int moe_megakernel_forward(const moe_problem_t *p, const void *x, const void *Wg
         case TK_LM: return launch_mega<Bf16Policy<CfgL>, Bf16Policy<CfgM>>(pl, a, st);
         default: return launch_mega<Bf16Policy<CfgS>, Bf16Policy<CfgS>>(pl, a, st);
     }
+}
+
+int moe_probe_mfma(const void *frag, int32_t iters, int32_t workgroups, float *sink, void *stream) {
+    if (!frag || !sink || iters < 1 || workgroups < 1 || workgroups > 65536) return MOE_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(k_probe_mfma, dim3(workgroups), dim3(kThreads), 0, (hipStream_t)stream, (const uint4 *)frag, iters, sink);
+    return hip_ok(hipGetLastError());
 }
 
 int moe_combine(const moe_problem_t *p, const void *staging, const uint32_t *flags, const int32_t *slot_flag,
