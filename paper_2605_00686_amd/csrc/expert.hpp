@@ -444,7 +444,7 @@ __device__ void publish_tile(const KArgs &a, const TileInfo &ti, char *smem) {
                         const int gb = __shfl(gbeg, src, 64), ge = __shfl(gend, src, 64), gi = __shfl(gid, src, 64);
                         // every tile counted for this group was released (device scope) by its
                         // writer before it was counted
-                        fence_acquire_no_invalidate();
+                        fence_acquire(0);
                         fence_release(sys);  // the one fence of this group
                         for (int fi = gb + lane; fi < ge; fi += 64) st_relaxed(&a.flags[fi], a.epoch, sys);
                         if (lane == 0)
@@ -588,23 +588,9 @@ static __device__ __attribute__((noinline)) void tile_stage(KArgsAddr args, u32 
             } else {
                 const TileInfo ti = single ? decode_block_tile<SMALL>(a, tb, one_a, one_b, P::BN2, a.d)
                                            : decode_tile<SMALL>(a, tb, tq, i, a.tl.NT2, P::BN2, a.d);
-                // h rows are written once, by GEMM1 tiles that released them before counting themselves.  When a
-                // row of h is not a whole number of cache lines, the last line of the neighbouring row block may
-                // hold this block's first row, fetched by that block's tiles before the row was written: only
-                // then is an invalidating acquire needed
-                const bool lines = a.h_rows_whole_lines != 0;
-                if (tid == 0) {
-                    sl->ok = (single || (lines ? wait_ge<false>(c, &a.h_ready[ti.rb], (u32)a.tl.NT1, a.wait_ticks)
-                                               : wait_ge<true>(c, &a.h_ready[ti.rb], (u32)a.tl.NT1, a.wait_ticks)))
-                                 ? 1
-                                 : 0;
-                }
-                if (single) {
-                    if (lines)
-                        fence_acquire_no_invalidate();
-                    else
-                        fence_acquire(0);
-                }
+                // h rows were released (agent scope) by their GEMM1 tiles before those counted themselves
+                if (tid == 0) sl->ok = (single || wait_ge(c, &a.h_ready[ti.rb], (u32)a.tl.NT1, a.wait_ticks)) ? 1 : 0;
+                if (single) fence_acquire(0);
                 __syncthreads();
                 MOE_TT(c, 5);
                 if (sl->ok)

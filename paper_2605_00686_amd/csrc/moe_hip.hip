@@ -488,7 +488,6 @@ static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
     a->group_size = p.group_size;
     a->wait_ticks = p.wait_ticks ? (u64)p.wait_ticks : kWaitTicks;
     a->scheduler = p.scheduler;
-    a->h_rows_whole_lines = ((size_t)p.f * elem_size(p.dtype)) % 128 == 0 ? 1 : 0;
     a->N = pl.N; a->NP = pl.NP; a->capacity = p.capacity; a->per_dest = pl.per_dest; a->ncb = pl.ncb;
     a->nPB = pl.nPB; a->nRT = pl.nRT; a->nCT = pl.nCT; a->comb_tokens = pl.comb_tokens;
     a->seg_from_blocks = (pl.per_dest % kPermBlock == 0) ? 1 : 0;
