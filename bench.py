@@ -36,7 +36,8 @@ SECONDARY_WORKLOAD = "cfg2"
 # WRITE_SIZE, each scaled by what the counter reads for a plain copy of known size).  Not measured by this
 # script: taken from the named summary under profiles/; a workload without one reports null.
 MEASURED_TRAFFIC = {
-    "cfg2": (1.853e9, "profiles/megakernel_cfg2_hbm_traffic.txt"),
+    "cfg2": (1.849e9, "profiles/megakernel_cfg2_hbm_traffic.txt"),
+    "cfg4": (2.063e10, "profiles/megakernel_cfg4_hbm_traffic.txt"),
 }
 
 
