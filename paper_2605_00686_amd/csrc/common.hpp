@@ -75,6 +75,7 @@ struct KArgs {
     int N, per_dest, ncb;  // slots, tokens per destination, column blocks per row
     int nPB, nRT, nCT;     // permutation blocks, gate tasks, combine tasks
     int comb_tokens;       // tokens per combine task
+    int disp_tokens;       // tokens per workgroup of the standalone dispatch's row movement
     int seg_from_blocks;   // destinations are whole permutation blocks: the plan derives seg_cnt from blk_hist
     Tiling tl;
     // front task ranges of the persistent scheduler: [gate-weight transposition | route | plan |

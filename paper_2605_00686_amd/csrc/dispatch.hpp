@@ -408,7 +408,13 @@ __device__ void gather_rows(const KArgs &a, int first, int stride, size_t row_by
 // position reads N rows, most of them from cache, and the chip then moves the written rows at barely half
 // the rate).  Used while N x workgroups stays small enough for the redundant counting to hide behind the row
 // movement of the other workgroups of a CU; larger problems take the histogram form.
-constexpr int kScatterTokens = 16;
+constexpr int kScatterTokens = 16;  // at most; fewer when there are few tokens (see scatter_tokens)
+// tokens per workgroup of the row movement: 16, or as many as still give about 256 workgroups
+__host__ __device__ inline int scatter_tokens(int T) {
+    int t = kScatterTokens;
+    while (t > 1 && (T + t - 1) / t < 256) t >>= 1;
+    return t;
+}
 
 // copies of the LDS counters that lanes are spread over, so that few experts do not serialise the LDS atomics
 __host__ __device__ inline int count_copies(int E) {
@@ -428,16 +434,19 @@ __device__ __forceinline__ void store_row16(char *p, const uint4 &v) {
         __builtin_nontemporal_store(w, (u32x4_t *)p);
 }
 
-// rows of tokens t0 .. t0+nt-1 to the sorted positions pos[tl*k + j] (LDS): one wavefront per token, each piece
-// loaded once and stored k times, four 16-byte loads in flight per lane
+// rows of tokens t0 .. t0+nt-1 to the sorted positions pos[tl*k + j] (LDS): a wavefront takes 4 KB of a token's row
+// at a time (the four wavefronts share a row when the workgroup has fewer than four tokens), each piece loaded once
+// and stored k times, four 16-byte loads in flight per lane
 template <int STORE>
 __device__ __forceinline__ void scatter_rows(const KArgs &a, int t0, int nt, const int *pos, size_t row_bytes) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int pieces = (int)(row_bytes / 16), k = a.k;
     char *xp = (char *)a.x_perm;
-    for (int tl = wave; tl < nt; tl += 4) {
+    // with four tokens or more a wavefront owns whole rows; with fewer the wavefronts share each row's chunks
+    const int tstep = nt >= 4 ? 4 : 1, cstep = nt >= 4 ? 256 : 1024;
+    for (int tl = nt >= 4 ? wave : 0; tl < nt; tl += tstep) {
         const uint4 *src = (const uint4 *)((const char *)a.x + (size_t)(t0 + tl) * row_bytes);
-        for (int c = lane; c < pieces; c += 256) {
+        for (int c = (nt >= 4 ? 0 : wave * 256) + lane; c < pieces; c += cstep) {
             uint4 v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u)
@@ -459,7 +468,7 @@ __device__ __forceinline__ void dispatch_fused_task(const KArgs &a, int b, size_
     __shared__ int s_pos[kScatterTokens * 32];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int E = a.E, k = a.k, N = a.N;
-    const int t0 = b * kScatterTokens, nt = min(kScatterTokens, a.T - t0), s0 = t0 * k;
+    const int t0 = b * a.disp_tokens, nt = min(a.disp_tokens, a.T - t0), s0 = t0 * k;
     const int C = count_copies(E);
     s_bef[tid] = 0;
     s_aft[tid] = 0;
@@ -558,7 +567,7 @@ __device__ __forceinline__ void dispatch_fused_task(const KArgs &a, int b, size_
 template <int STORE>
 __device__ __forceinline__ void scatter_task(const KArgs &a, int b, size_t row_bytes) {
     __shared__ int s_pos[kScatterTokens * 32];
-    const int t0 = b * kScatterTokens, nt = min(kScatterTokens, a.T - t0);
+    const int t0 = b * a.disp_tokens, nt = min(a.disp_tokens, a.T - t0);
     for (int q = threadIdx.x; q < nt * a.k; q += kThreads) {
         const int p = a.inv_perm[(size_t)t0 * a.k + q];
         s_pos[q] = min(max(p, 0), a.NP - 1);  // (a position is never followed out of x_perm)

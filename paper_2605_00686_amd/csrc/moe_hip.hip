@@ -491,6 +491,7 @@ static void fill_args(const Plan &pl, void *workspace, KArgs *a) {
     a->N = pl.N; a->NP = pl.NP; a->capacity = p.capacity; a->per_dest = pl.per_dest; a->ncb = pl.ncb;
     a->nPB = pl.nPB; a->nRT = pl.nRT; a->nCT = pl.nCT; a->comb_tokens = pl.comb_tokens;
     a->seg_from_blocks = (pl.per_dest % kPermBlock == 0) ? 1 : 0;
+    a->disp_tokens = scatter_tokens(p.T);
     a->tl = pl.tl;
     a->t_gate = 0;  // the megakernel adds the transposition tasks when it has a gate to compute
     a->t_plan = pl.nRT;
@@ -715,7 +716,7 @@ static int dispatch_launches(const Plan &pl, const KArgs &a, bool short_only, hi
     if (ggrid > 8192) ggrid = 8192;
     // rows that do not fit the 256 MB memory-side cache are stored past it; others are written through
     const bool past_cache = (size_t)pl.NP * row_bytes > ((size_t)192 << 20);
-    const int sgrid = (p->T + kScatterTokens - 1) / kScatterTokens;
+    const int sgrid = (p->T + a.disp_tokens - 1) / a.disp_tokens;
     // rows by token (read once, stored k times): ragged layout; the padded layout's histogram form keeps the gather
     // by sorted position, which also zeroes the unused rows
     auto move_rows = [&]() {
