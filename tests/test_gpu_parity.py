@@ -684,3 +684,17 @@ def test_expired_waits_drain_the_kernel(scheduler):
     buf.flags.zero_()
     p, buf = run_forward(B, inp, 1, 0, epoch=3, buf=buf, scheduler=scheduler)
     check_against_oracle(B, inp, p, buf, 1, ref)
+
+
+def test_probe_mfma_runs_and_keeps_its_work():
+    """The measurement aid: launches, writes one float per thread, and the sums are what 16 products per round of the
+    given fragments add up to (all-ones operands: every accumulator element gains 16 per product)."""
+    B = _binding()
+    frag = torch.ones(4096, dtype=torch.bfloat16, device="cuda")
+    sink = torch.full((8 * 256,), float("nan"), dtype=torch.float32, device="cuda")
+    B.moe_probe_mfma(frag, 3, 8, sink)
+    torch.cuda.synchronize()
+    # a lane holds 16 accumulator values of each of the 16 independent products; each value = rounds * K(16) * 1 * 1
+    assert torch.equal(sink, torch.full_like(sink, 3 * 16.0 * 16 * 16))
+    with pytest.raises(B.MoeError):
+        B.moe_probe_mfma(frag, 0, 8, sink)
