@@ -179,7 +179,8 @@ def run_workload(name, args, B, torch, W, steps, warmup, with_cpu, with_ops, cal
     cfg = W.config(name)
     # tens of GB of weights are drawn in GPU memory (seconds instead of minutes on the host)
     big = 3 * cfg["E"] * cfg["d"] * cfg["f"] * elem_bytes(cfg) > 8e9
-    inp = W.make_inputs(name, device="cuda" if big and cfg["prerouted"] is None else "cpu")
+    inp = W.make_inputs(dict(W.CONFIGS[name], tile_m=args.tile_m) if args.tile_m else name,
+                        device="cuda" if big and cfg["prerouted"] is None else "cpu")
     cfg = inp["cfg"]
     mode = B.MOE_SIGNAL_PER_DEST if args.signal_mode == "per_dest" else B.MOE_SIGNAL_PER_TILE
     scope = B.MOE_SCOPE_AGENT if args.scope == "agent" else B.MOE_SCOPE_SYSTEM
@@ -187,7 +188,8 @@ def run_workload(name, args, B, torch, W, steps, warmup, with_cpu, with_ops, cal
     def make_problem(capacity):
         return B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
                          tile_n=cfg["tile_n"], signal_mode=mode, fence_scope=scope, epoch=1, group_size=args.group_size,
-                         scheduler=1 if args.scheduler == "ready_queue" else 0, capacity=capacity)
+                         scheduler=1 if args.scheduler == "ready_queue" else 0, capacity=capacity,
+                         fuse_ffn=1 if args.fuse_ffn else 0)
 
     def fresh_buffers(p):
         buf = B.Buffers(p)
@@ -290,6 +292,10 @@ def main():
     ap.add_argument("--capacity", type=int, default=0,
                     help="rows per expert in the padded layout of the sorted order (0 = ragged layout; -1 = the largest "
                          "expert's row count of this workload, rounded up to a multiple of 64)")
+    ap.add_argument("--fuse-ffn", action="store_true",
+                    help="a workgroup takes a row block through both GEMMs with h in LDS (f <= 768, tile_m <= 64; see "
+                         "--tile-m) instead of two tile passes with h in the workspace")
+    ap.add_argument("--tile-m", type=int, default=0, help="publish tile rows (0 = the workload's own)")
     ap.add_argument("--cpu-tokens", type=int, default=0, help="tokens for the CPU baseline (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-secondary", action="store_true",

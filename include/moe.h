@@ -125,6 +125,15 @@ typedef struct {
                               /* the workspace must be initialised again.  (A tiny  */
                               /* value is how a test forces that path from the      */
                               /* host.)                                             */
+    int32_t fuse_ffn;         /* moe_megakernel_forward only.  0: GEMM1 and GEMM2   */
+                              /* are separate tile passes with h in the workspace.  */
+                              /* 1: a workgroup takes a row block of 32 or 64 rows  */
+                              /* through both GEMMs and keeps the block's h in LDS  */
+                              /* (section 2.3: a tile traverses GEMM -> activation  */
+                              /* -> GEMM).  bf16 only, MOE_SCHED_STATIC only,       */
+                              /* tile_m <= 64, and rows * f * 2 bytes must fit the  */
+                              /* LDS beside the stage buffers (f <= 768), else      */
+                              /* MOE_ERR_UNSUPPORTED.  Same results                 */
 } moe_problem_t;
 
 /* number of 64-bit counters moe_megakernel_forward writes to `stats` */

@@ -31,7 +31,8 @@ class MoeProblem(ctypes.Structure):
                                                                                  ("group_size", ctypes.c_int32),
                                                                                  ("scheduler", ctypes.c_int32),
                                                                                  ("capacity", ctypes.c_int32),
-                                                                                 ("wait_ticks", ctypes.c_uint32)]
+                                                                                 ("wait_ticks", ctypes.c_uint32),
+                                                                                 ("fuse_ffn", ctypes.c_int32)]
 
 
 class MoeError(RuntimeError):
@@ -63,13 +64,14 @@ for _n in ("moe_workspace_init", "moe_route", "moe_dispatch", "moe_dispatch_noal
 
 
 def problem(T, d, E, k, f, R, dtype, tile_m=0, tile_n=0, signal_mode=MOE_SIGNAL_PER_DEST,
-            fence_scope=MOE_SCOPE_AGENT, epoch=1, group_size=0, scheduler=0, capacity=0, wait_ticks=0) -> MoeProblem:
+            fence_scope=MOE_SCOPE_AGENT, epoch=1, group_size=0, scheduler=0, capacity=0, wait_ticks=0,
+            fuse_ffn=0) -> MoeProblem:
     if isinstance(dtype, torch.dtype):
         dtype = MOE_DT_F32 if dtype == torch.float32 else MOE_DT_BF16
     elif isinstance(dtype, str):
         dtype = MOE_DT_F32 if dtype == "f32" else MOE_DT_BF16
     return MoeProblem(T, d, E, k, f, R, dtype, tile_m, tile_n, signal_mode, fence_scope, epoch, group_size, scheduler,
-                      capacity, wait_ticks)
+                      capacity, wait_ticks, fuse_ffn)
 
 
 def _ptr(t):

@@ -76,6 +76,8 @@ struct KArgs {
     int nPB, nRT, nCT;     // permutation blocks, gate tasks, combine tasks
     int comb_tokens;       // tokens per combine task
     int disp_tokens;       // tokens per workgroup of the standalone dispatch's row movement
+    int fused;             // moe_problem_t::fuse_ffn: a workgroup takes a row block through both GEMMs, h in LDS
+    int fused_h_off;       // ... LDS offset of that h buffer [row block rows][f]
     int seg_from_blocks;   // destinations are whole permutation blocks: the plan derives seg_cnt from blk_hist
     Tiling tl;
     // front task ranges of the persistent scheduler: [gate-weight transposition | route | plan |

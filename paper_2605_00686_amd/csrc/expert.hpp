@@ -12,6 +12,8 @@ namespace moe {
 template <class C>
 struct Bf16Policy {
     using ET = bf16_t;
+    using Cfg = C;
+    static constexpr bool FUSED = false;
     static constexpr int BM = C::BM, BN1 = C::BN / 2, BN2 = C::BN;
     static constexpr int C_STRIDE = C::C_STRIDE;
     static constexpr int SMEM_MAIN = C::SMEM_MAIN;
@@ -25,6 +27,7 @@ struct Bf16Policy {
 };
 struct F32Policy {
     using ET = float;
+    static constexpr bool FUSED = false;
     static constexpr int BM = TileF32::BM, BN1 = TileF32::BN, BN2 = TileF32::BN;
     static constexpr int C_STRIDE = TileF32::C_STRIDE;
     static constexpr int SMEM_MAIN = TileF32::SMEM_MAIN;
@@ -34,6 +37,11 @@ struct F32Policy {
                                                 char *smem, Hook while_loading) {
         gemm_tile_f32<GATED>(rp, B0, B1, ldb, ncols, K, smem, while_loading);
     }
+};
+// The fused FFN (moe_problem_t::fuse_ffn): same main loops, other tile loop (see fused_stage)
+template <class C>
+struct FusedPolicy : Bf16Policy<C> {
+    static constexpr bool FUSED = true;
 };
 // LDS after the GEMM region: per-row slot / destination, publish row-tile list
 template <class P>
@@ -45,6 +53,10 @@ constexpr int tile_smem_bytes() {
 using CfgL = TileCfg<4, 4, 2, 2, 32, 4>;  // 256 x 256, wavefront 128 x 128
 using CfgM = TileCfg<2, 4, 2, 2, 64, 3>;  // 128 x 256, wavefront  64 x 128
 using CfgS = TileCfg<1, 2, 1, 4, 64, 4>;  //  32 x 256, wavefront  32 x  64, deep pipeline: weight streaming
+
+// row blocks of the fused FFN: short enough for a block's h to stay in LDS beside three stages
+using CfgFS = TileCfg<1, 2, 1, 4, 64, 3>;  // 32 x 256, wavefront 32 x 64 (decode-sized experts)
+using CfgFM = TileCfg<2, 2, 1, 4, 32, 3>;  // 64 x 256, wavefront 64 x 64
 
 constexpr int kTileGroupRows = 4, kTileGroupCols = 8;  // see decode_tile
 
@@ -610,6 +622,104 @@ static __device__ __attribute__((noinline)) void tile_stage(KArgsAddr args, u32 
 #ifdef MOE_TILE_TIMING
             if (tid == 0) atomicMax(&c->dbg[24 + q], now_ticks() - c->t0);
 #endif
+        }
+    }
+}
+
+// ---- the fused FFN (moe_problem_t::fuse_ffn; paper section 2.3: a tile traverses dispatch -> GEMM -> activation ->
+// GEMM).  A workgroup takes one row block of an expert (32 or 64 rows) through the whole FFN: every column tile of
+// GEMM1 + SwiGLU writes its piece of h into an LDS buffer laid out like staged A tiles, a barrier, then every column
+// tile of GEMM2 reads A from that buffer and streams only W2; each y tile is published as usual.  h never leaves
+// the CU and no workgroup waits for another between the two GEMMs; the price is that every row block streams its
+// expert's W1, W3 and W2 by itself (row blocks of one expert are neighbours in an XCD's list, so the L2 serves the
+// repeats), on matrix-core tiles of 32 or 64 rows.  Row blocks come from the same per-XCD lists as the tiles of the
+// unfused path (list 0, one entry per row block).
+template <class P>
+__device__ __forceinline__ void fused_block(const KArgs &a, const TileInfo &rb, char *smem) {
+    using C = typename P::Cfg;
+    using ET = typename P::ET;
+    char *hres = smem + a.fused_h_off;
+    const ET *x = (const ET *)a.x;
+    const int N = a.N;
+    auto xrow = [&](int r) {
+        int s = a.perm[rb.row0 + min(r, rb.nrows - 1)];
+        s = min(max(s, 0), N - 1);
+        return x + (size_t)(s / a.k) * a.d;
+    };
+    for (int ct = 0; ct < a.tl.NT1; ++ct) {
+        const int n0 = ct * P::BN1, ncols = min(P::BN1, a.f - n0);
+        const size_t wofs = (size_t)rb.e * a.d * a.f + n0;
+        gemm_tile_bf16<C, true, true, false>(xrow, (const ET *)a.W1 + wofs, (const ET *)a.W3 + wofs, a.f, ncols, a.d, smem,
+                                             [] {}, hres, n0, a.f);
+        if (threadIdx.x == 0) atomicAdd(&a.ctrl->stats[4], 1ull);
+    }
+    // (the last tile's epilogue ended with a barrier: h is complete for every wavefront)
+    TileInfo ti = rb;
+    publish_prepare<P>(a, ti, smem);
+    for (int ct = 0; ct < a.tl.NT2; ++ct) {
+        ti.n0 = ct * P::BN2;
+        ti.ncols = min(P::BN2, a.d - ti.n0);
+        const ET *B0 = (const ET *)a.W2 + (size_t)rb.e * a.f * a.d + ti.n0;
+        gemm_tile_bf16<C, false, false, true>([](int) { return (const ET *)nullptr; }, B0, B0, a.d, ti.ncols, a.f, smem, [] {},
+                                              hres, 0, 0);
+        publish_tile<P>(a, ti, smem);
+        if (threadIdx.x == 0) atomicAdd(&a.ctrl->stats[5], 1ull);
+    }
+}
+
+template <class P>
+static __device__ __attribute__((noinline)) void fused_stage(KArgsAddr args, u32 smem_off, int home, int n_rb,
+                                                            volatile int *caller_local) {
+    KArgs a = load_kernel_args(args);
+    mark_global(a);
+    char *smem = lds_at((u32)uniform((int)smem_off));
+    home = uniform(home), n_rb = uniform(n_rb);
+    const int tid = threadIdx.x;
+    Ctrl *c = a.ctrl;
+    StageLds *sl = (StageLds *)(smem + a.sched_lds_off);
+    const Tables tb = decode_tables(a, smem, n_rb, 0);
+    const u64 t0 = kernel_start_ticks(c);
+    *caller_local = 4;  // (see the call sites of tile_stage)
+    while (true) {
+        // the first list, from this XCD's on, that still has row blocks
+        __syncthreads();
+        if (tid < 64) {
+            bool has = false;
+            if (tid < kTileQueues) {
+                const int qq = (home + tid) % kTileQueues;
+                const TileQueue t2 = tile_queue(a, n_rb, 0, qq);
+                has = ld_relaxed_agent(&c->tile_next[0][qq]) < (u32)(t2.r1 - t2.r0);
+            }
+            const u64 m = __ballot(has);
+            if (tid == 0) sl->pick = m ? (home + __ffsll((long long)m) - 1) % kTileQueues : -1;
+        }
+        __syncthreads();
+        const int q = uniform(sl->pick);
+        if (q < 0) break;
+        const TileQueue tq = tile_queue(a, n_rb, 0, q);
+        const int n = tq.r1 - tq.r0;
+        if (tid == 0) sl->next = (int)atomicAdd(&c->tile_next[0][q], 1u);
+        __syncthreads();
+        int i = uniform(sl->next);
+        while (i < n) {
+            u32 next = 0;
+            if (tid == 0) next = atomicAdd(&c->tile_next[0][q], 1u);  // consumed at the end of the block
+            TileInfo rb;
+            rb.rb = tq.r0 + i;
+            rb.e = tb.rb_expert[rb.rb];
+            rb.lrow0 = (rb.rb - tb.rb_base[rb.e]) * a.tl.BM;
+            rb.row0 = tb.offsets[rb.e] + rb.lrow0;
+            rb.nrows = min(a.tl.BM, tb.counts[rb.e] - rb.lrow0);
+            rb.n0 = 0, rb.ncols = 0, rb.valid = true;
+            fused_block<P>(a, rb, smem);
+            __syncthreads();
+            if (tid == 0) {
+                mark_phase_end(c, 3, t0);
+                mark_phase_end(c, 4, t0);
+                sl->next = (int)next;
+            }
+            __syncthreads();
+            i = uniform(sl->next);
         }
     }
 }

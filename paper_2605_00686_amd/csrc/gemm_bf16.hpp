@@ -73,9 +73,18 @@ __device__ __forceinline__ void wait_vmcnt() {
 //   while_loading(): called by every thread once the first stages' loads are in flight, for
 //              work of the caller that fits into that trip to memory (it may use barriers and
 //              LDS beyond SMEM_MAIN)
-template <class C, bool GATED, class RowPtr, class Hook>
+// Two variations for a workgroup that takes a row block through both GEMMs of the FFN with the intermediate h
+// kept in LDS (paper section 2.3: a tile traverses GEMM -> activation -> GEMM):
+//   HRES: (GATED only) the result is not left in a C tile but written into `res`, an LDS buffer that holds the
+//         row block's h in the layout of A stages: stage s (columns [s*BK, (s+1)*BK) of h) at res + s*A_BYTES,
+//         rows of A_ROW bytes, swizzled like a staged A tile; n0 = first h column of this tile, ntot = f.
+//   ARES: A is not loaded: stage s of A is read from res + s*A_BYTES (written by HRES tiles before); only the
+//         weights stream through the stage buffers (their A parts stay unused); rowptr is not called.
+template <class C, bool GATED, bool HRES = false, bool ARES = false, class RowPtr, class Hook>
 __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1, int ldb, int ncols,
-                               int K, char *smem, Hook while_loading) {
+                               int K, char *smem, Hook while_loading, char *res = nullptr, int n0 = 0, int ntot = 0) {
+    static_assert(!(HRES && !GATED) && !(HRES && ARES), "h is produced by the gated GEMM and consumed by the other one");
+    constexpr int LPSX = ARES ? C::NBI : C::LPS;  // loads per wavefront per stage
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / C::WN, wn = wave % C::WN;
     constexpr int HALF = C::BN / 2;
@@ -95,7 +104,7 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
         const int instr = (uw * C::NAI + i) % C::A_INSTR;
         const int row = instr * RPI + lane / CPRA;
         const int chunk = (lane % CPRA) ^ a_swz(row);
-        a_ptr[i] = rowptr(row) + chunk * 8;
+        a_ptr[i] = ARES ? nullptr : rowptr(row) + chunk * 8;
         a_dst[i] = instr * 1024;
     }
     // ---- B loads.  Instruction covers 2 weight rows (2 x 512 bytes); weight row
@@ -160,25 +169,25 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
     auto issue_one = [&](int kt, int buf, int i) {
         const u32 sa = lds_base + buf * C::STAGE;
         const u32 sb = sa + C::A_BYTES;
-        if (i < C::NAI) {
+        if (!ARES && i < C::NAI) {
             dma16(a_ptr[i] + kt * C::BK, sa + a_dst[i]);
         } else {
-            const int j = i - C::NAI;
+            const int j = ARES ? i : i - C::NAI;
             const int r2 = (uw * C::NBI + j) * 2;  // first of the two weight rows of this instruction
             dma16(b_ptr[j & 1] + (size_t)(kt * C::BK + r2) * ldb, sb + r2 * (C::BN * 2));
         }
     };
     auto issue_loads = [&](int kt, int buf) {
 #pragma unroll
-        for (int i = 0; i < C::LPS; ++i) issue_one(kt, buf, i);
+        for (int i = 0; i < LPSX; ++i) issue_one(kt, buf, i);
     };
     constexpr int KK = C::BK / 16;  // MFMA reduction steps per stage
     struct Frag {
         bf16x8_t a[C::MB], b[C::NB];
     };
-    auto load_frag = [&](int buf, int kk, Frag &f) {
-        const char *sa = smem + buf * C::STAGE;
-        const char *sb = sa + C::A_BYTES;
+    auto load_frag = [&](int buf, int kt, int kk, Frag &f) {  // fragments of step kk of stage kt, which sits in buffer buf
+        const char *sa = ARES ? res + kt * C::A_BYTES : smem + buf * C::STAGE;
+        const char *sb = smem + buf * C::STAGE + C::A_BYTES;
 #pragma unroll
         for (int mb = 0; mb < C::MB; ++mb) {
             const int off = (a_rd_row + mb * 32) * C::A_ROW + ((((kk << 1) | a_rd_half) ^ a_rd_swz) << 4);
@@ -208,10 +217,10 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
     // takes to accept it (about 2000 cycles for a whole 256 x 256 stage), so the
     // loads are dealt out over the steps and the scheduler is asked to interleave:
     // one LDS read behind each MFMA, one global load every few MFMAs.
-    constexpr int LPK = (C::LPS + KK - 1) / KK;  // refill loads per step
+    constexpr int LPK = (LPSX + KK - 1) / KK;  // refill loads per step
     constexpr int NREAD = C::MB + 2 * C::NB, NMFMA = C::MB * C::NB;
-    auto step = [&](int frag_buf, int frag_kk, Frag &nxt, const Frag &cur, int fill_kt, int fill_buf, int part) {
-        load_frag(frag_buf, frag_kk, nxt);
+    auto step = [&](int frag_buf, int frag_kt, int frag_kk, Frag &nxt, const Frag &cur, int fill_kt, int fill_buf, int part) {
+        load_frag(frag_buf, frag_kt, frag_kk, nxt);
 #pragma unroll
         for (int mb = 0; mb < C::MB; ++mb)
 #pragma unroll
@@ -220,7 +229,7 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
                 // share j of this step's loads goes in front of MFMA number j*NMFMA/LPK
 #pragma unroll
                 for (int j = 0; j < LPK; ++j)
-                    if ((j * NMFMA) / LPK == i && part * LPK + j < C::LPS) issue_one(fill_kt, fill_buf, part * LPK + j);
+                    if ((j * NMFMA) / LPK == i && part * LPK + j < LPSX) issue_one(fill_kt, fill_buf, part * LPK + j);
                 acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.b[nb], cur.a[mb], acc[mb][nb], 0, 0, 0);
             }
 #pragma unroll
@@ -245,43 +254,43 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
 #pragma unroll
     for (int s = 0; s + 1 < C::NS; ++s) issue_loads(min(s, nk - 1), s);
     int fill_kt = min(C::NS - 1, nk - 1), fill_buf = C::NS - 1;
-    constexpr int PART0 = LPK < C::LPS ? LPK : C::LPS;
+    constexpr int PART0 = LPK < LPSX ? LPK : LPSX;
 #pragma unroll
     for (int i = 0; i < PART0; ++i) issue_one(fill_kt, fill_buf, i);
     // (loads the caller issues here are younger than the stage loads: if they are still in
     // flight at a vmcnt wait below, that wait only becomes stricter)
     while_loading();
-    wait_vmcnt<(C::NS - 2) * C::LPS + PART0>();
+    wait_vmcnt<(C::NS - 2) * LPSX + PART0>();
     __syncthreads();
     Frag f0, f1;
-    load_frag(0, 0, f0);
+    load_frag(0, 0, 0, f0);
     int buf = 0;
     static_assert(KK % 2 == 0, "fragment double buffer assumes an even number of steps per stage");
     // steps 0 .. KK-2 of a stage; they also carry shares 1 .. KK-1 of the refill in progress
-    auto main_steps = [&](int b) {
+    auto main_steps = [&](int b, int kt) {
 #pragma unroll
         for (int kk = 0; kk + 1 < KK; ++kk) {
             if (kk & 1)
-                step(b, kk + 1, f0, f1, fill_kt, fill_buf, kk + 1);
+                step(b, kt, kk + 1, f0, f1, fill_kt, fill_buf, kk + 1);
             else
-                step(b, kk + 1, f1, f0, fill_kt, fill_buf, kk + 1);
+                step(b, kt, kk + 1, f1, f0, fill_kt, fill_buf, kk + 1);
         }
     };
     // KK is even: a stage starts in f0 and its last step multiplies f1
     for (int kt = 0; kt + 1 < nk; ++kt) {
-        main_steps(buf);
+        main_steps(buf, kt);
         // last step of the stage: cross into the next stage first.  Stage kt+1 must
         // have landed; the NS-2 stages issued after it may stay in flight.
-        wait_vmcnt<(C::NS - 2) * C::LPS>();
+        wait_vmcnt<(C::NS - 2) * LPSX>();
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // this stage's fragments are in registers
         __syncthreads();
         const int nbuf = (buf + 1 == C::NS) ? 0 : buf + 1;
         fill_kt = min(kt + C::NS, nk - 1);
         fill_buf = buf;
-        step(nbuf, 0, f0, f1, fill_kt, fill_buf, 0);
+        step(nbuf, kt + 1, 0, f0, f1, fill_kt, fill_buf, 0);
         buf = nbuf;
     }
-    main_steps(buf);
+    main_steps(buf, nk - 1);
     mfma_all(f1);
     wait_vmcnt<0>();  // nothing may still be landing in LDS when the C tile is written over the stage buffers
     __syncthreads();
@@ -290,6 +299,31 @@ __device__ void gemm_tile_bf16(RowPtr rowptr, const bf16_t *B0, const bf16_t *B1
     // MFMA block (mb, nb) and register group vq, output row (l & 31) and the 4
     // consecutive columns 8*vq + 4*(l >> 5) .. +3 of that block.
     const int c_row = wm * 32 * C::MB + (lane & 31);
+    if (HRES) {
+        // h of the row block, as the A operand of the GEMM that follows: column c of h belongs to stage c / BK
+#pragma unroll
+        for (int mb = 0; mb < C::MB; ++mb) {
+            const int row = c_row + mb * 32;
+#pragma unroll
+            for (int nb = 0; nb < C::NB / 2; ++nb)
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int col = n0 + wn * (C::BNW / 2) + nb * 32 + 8 * vq + 4 * (lane >> 5);
+                    if (col < ntot) {
+                        const f32x16_t &g = acc[mb][nb];
+                        const f32x16_t &u = acc[mb][nb + C::NB / 2];
+                        uint2 o;
+                        o.x = pack_bf16x2(silu_mul(g[4 * vq], u[4 * vq]), silu_mul(g[4 * vq + 1], u[4 * vq + 1]));
+                        o.y = pack_bf16x2(silu_mul(g[4 * vq + 2], u[4 * vq + 2]), silu_mul(g[4 * vq + 3], u[4 * vq + 3]));
+                        const int cin = col % C::BK;
+                        *(uint2 *)(res + (col / C::BK) * C::A_BYTES + row * C::A_ROW + (((cin >> 3) ^ a_swz(row)) << 4) +
+                                   (cin & 7) * 2) = o;
+                    }
+                }
+        }
+        __syncthreads();
+        return;
+    }
 #pragma unroll
     for (int mb = 0; mb < C::MB; ++mb) {
         char *crow = smem + (c_row + mb * 32) * C::C_STRIDE;

@@ -293,7 +293,11 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
         // callee-saved registers in these functions (they have one caller, which keeps nothing in them):
         // some 270 registers per lane through scratch memory, per call, otherwise.
         volatile int stage_mark = 0;
-        if (a.scheduler == MOE_SCHED_READY_QUEUE) {
+        if constexpr (P::FUSED) {
+            // ---- stage 2, fused: row blocks through both GEMMs, then combine
+            fused_stage<P>(kargs, lds, home, n_rb, &stage_mark);
+            combine_stage<ET>(a, smem);
+        } else if (a.scheduler == MOE_SCHED_READY_QUEUE) {
             // ---- stages 2 and 3 from the ready queues
             ready_queue_stage<P, PS, MIXED>(a, kargs, smem, home, n_rb, n_rbs, &stage_mark);
         } else {
@@ -350,6 +354,7 @@ __global__ __launch_bounds__(kThreads, P::MIN_WAVES) void k_megakernel(KArgs a) 
 // The standalone dispatch runs as one launch while (slots) x (workgroups of 16 tokens) is at most this: every
 // workgroup counts every slot, which hides behind the row movement up to about this much.
 constexpr long long kFusedDispatchWork = 64ll << 20;
+constexpr size_t kLdsBudget = 160 * 1024 - 256;  // dynamic LDS a kernel may ask for: the CU's 160 KB less the kernels' few static words
 constexpr int kMaxDevices = 16;  // devices the host-side launch memo covers (others ask the runtime on every call)
 
 static inline size_t align_up(size_t v, size_t al) { return (v + al - 1) / al * al; }
@@ -360,7 +365,8 @@ static int elem_size(int dtype) { return dtype == MOE_DT_F32 ? 4 : 2; }
 // into at most kGateSplitTasks tasks in all.
 constexpr int kGateSplitBlocks = 64, kGateSplitTasks = 256, kGateSplitMax = 16;
 
-enum TileKind { TK_F32 = 0, TK_LM = 1, TK_S = 3 };  // LM: 256-row tiles plus a 128-row tile for short tails
+// LM: 256-row tiles plus a 128-row tile for short tails; FS / FM: row blocks of the fused FFN (32 / 64 rows)
+enum TileKind { TK_F32 = 0, TK_LM = 1, TK_S = 3, TK_FS = 4, TK_FM = 5 };
 
 struct Plan {
     moe_problem_t p;
@@ -386,6 +392,8 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
     if (p->group_size < 0 || (p->group_size != 0 && p->signal_mode != MOE_SIGNAL_PER_DEST)) return MOE_ERR_INVALID_ARG;
     if (p->scheduler != MOE_SCHED_STATIC && p->scheduler != MOE_SCHED_READY_QUEUE) return MOE_ERR_INVALID_ARG;
     if (p->capacity < 0) return MOE_ERR_INVALID_ARG;
+    if (p->fuse_ffn != 0 && p->fuse_ffn != 1) return MOE_ERR_INVALID_ARG;
+    if (p->fuse_ffn && p->scheduler != MOE_SCHED_STATIC) return MOE_ERR_INVALID_ARG;
     if ((long long)p->E * p->capacity > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
     if (p->E > kMaxExperts || p->k > 32 || p->R > kMaxDest) return MOE_ERR_UNSUPPORTED;
     if ((long long)p->T * p->k > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
@@ -417,12 +425,20 @@ static int make_plan(const moe_problem_t *p, Plan *pl) {
         bm = TileF32::BM;
         pl->tl.BN1 = TileF32::BN;
         pl->tl.BN2 = TileF32::BN;
+    } else if (p->fuse_ffn) {
+        // the fused FFN: row blocks of 32 rows for decode-sized experts, else 64; the block's h must fit the LDS
+        // beside the stage buffers (checked at launch: MOE_ERR_UNSUPPORTED if it does not)
+        pl->kind = (avg < 96 && tm == 32) ? TK_FS : TK_FM;
+        bm = pl->kind == TK_FS ? CfgFS::BM : CfgFM::BM;
+        pl->tl.BN1 = 128;
+        pl->tl.BN2 = 256;
     } else {
         pl->kind = (avg >= 96 || tm > 32) ? TK_LM : TK_S;
         bm = pl->kind == TK_LM ? CfgL::BM : CfgS::BM;
         pl->tl.BN1 = 128;
         pl->tl.BN2 = 256;
     }
+    if (p->fuse_ffn && p->dtype != MOE_DT_BF16) return MOE_ERR_UNSUPPORTED;
     pl->tl.BMS = pl->kind == TK_LM ? CfgM::BM : 0;
     // few rows per expert: the layer streams weights (measured: about -1 % on cfg2; +2 to 4 % on cfg3 and cfg4,
     // which have thousands of rows per expert and are bound by the matrix cores, if it were applied there)
@@ -570,15 +586,21 @@ template <class P, class PS>
 static int launch_mega(const Plan &pl, const KArgs &a_in, hipStream_t st) {
     size_t smem = tile_smem_bytes<P>();
     if (tile_smem_bytes<PS>() > smem) smem = tile_smem_bytes<PS>();
+    KArgs a = a_in;
+    if (P::FUSED) {  // the row block's h, behind the GEMM region and the publish bookkeeping (the gate's LDS is free by then)
+        a.fused = 1;
+        a.fused_h_off = (int)align_up(smem, 16);
+        smem = a.fused_h_off + (size_t)P::BM * pl.p.f * elem_size(pl.p.dtype);
+        if (smem + sizeof(StageLds) + 16 > kLdsBudget) return MOE_ERR_UNSUPPORTED;
+    }
     const size_t rsm = route_smem_bytes(pl.p.E, elem_size(pl.p.dtype));
     if (a_in.Wg && rsm > smem) smem = rsm;
     if (a_in.WgT && screen_smem_bytes(pl.p.E) > smem) smem = screen_smem_bytes(pl.p.E);
     if (plan_smem(pl) > smem) smem = plan_smem(pl);
     // decode tables live behind everything else, for the life of the workgroup
-    KArgs a = a_in;
     const size_t tab_bytes = (size_t)(4 * (pl.p.E + 1) + pl.tl.maxRB + pl.p.E) * 4;
     a.tab_lds_off = 0;
-    if (tab_bytes <= 6 * 1024) {  // small enough that two workgroups of the 128-row tile still share a CU
+    if (tab_bytes <= 6 * 1024 && smem + tab_bytes + sizeof(StageLds) + 16 <= kLdsBudget) {  // small enough that two workgroups of the 128-row tile still share a CU
         a.tab_lds_off = (int)align_up(smem, 16);
         smem = a.tab_lds_off + tab_bytes;
     }
@@ -852,6 +874,8 @@ int moe_megakernel_forward(const moe_problem_t *p, const void *x, const void *Wg
     switch (pl.kind) {
         case TK_F32: return launch_mega<F32Policy, F32Policy>(pl, a, st);
         case TK_LM: return launch_mega<Bf16Policy<CfgL>, Bf16Policy<CfgM>>(pl, a, st);
+        case TK_FS: return launch_mega<FusedPolicy<CfgFS>, FusedPolicy<CfgFS>>(pl, a, st);
+        case TK_FM: return launch_mega<FusedPolicy<CfgFM>, FusedPolicy<CfgFM>>(pl, a, st);
         default: return launch_mega<Bf16Policy<CfgS>, Bf16Policy<CfgS>>(pl, a, st);
     }
 }

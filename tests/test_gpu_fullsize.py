@@ -33,13 +33,13 @@ def _tokens(name, cfg, counts, offsets, perm):
     return np.array(sorted(tok), dtype=np.int32)
 
 
-def _run(name, signal_mode, fence_scope, inp=None, buf=None, epoch=1, group_size=0, scheduler=0, capacity=0):
+def _run(name, signal_mode, fence_scope, inp=None, buf=None, epoch=1, group_size=0, scheduler=0, capacity=0, fuse_ffn=0):
     from paper_2605_00686_amd import binding as B
     inp = inp or W.make_inputs(name)
     cfg = inp["cfg"]
     p = B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
                   tile_n=cfg["tile_n"], signal_mode=signal_mode, fence_scope=fence_scope, epoch=epoch,
-                  group_size=group_size, scheduler=scheduler, capacity=capacity)
+                  group_size=group_size, scheduler=scheduler, capacity=capacity, fuse_ffn=fuse_ffn)
     buf = buf or B.Buffers(p)
     dev = inp.setdefault("_dev", {n: (inp[n].cuda() if inp[n] is not None else None)
                                   for n in ("x", "Wg", "gate_bias", "W1", "W3", "W2")})
@@ -126,6 +126,10 @@ def test_fullsize_parity(name):
     assert buf.stats.cpu().numpy()[16] > 0
     B, inp, p, buf = _run(name, 1, 0, inp=inp, buf=buf, epoch=7)
     _check(B, inp, p, buf, 1, name, cache)
+    if name == "cfg8":  # the fused FFN (row blocks of 32 rows, h in LDS) on the same buffers, both signaling modes
+        for epoch, mode in ((9, 1), (10, 0)):
+            B, inp, p, buf = _run(name, mode, 0, inp=inp, buf=buf, epoch=epoch, fuse_ffn=1)
+            _check(B, inp, p, buf, mode, name, cache)
     if name in ("cfg2", "cfg5"):  # the padded layout at full size (its own buffers: h and perm are larger)
         cap = int(cache["ref"]["counts"].max()) + 8
         B, inp, p, buf = _run(name, 1, 0, inp=inp, epoch=8, capacity=cap)
@@ -146,4 +150,18 @@ def test_fullsize_weights_beyond_2g_elements():
     hot = np.unique(cache["ref"]["idx"][cache["ref"]["tok"]])
     assert hot.max() >= 147, "no checked token reaches an expert whose weights start beyond 2^31 elements"
     B, inp, p, buf = _run(name, 1, 0, inp=inp, buf=buf, epoch=2, scheduler=1)
+    _check(B, inp, p, buf, 1, name, cache)
+
+
+def test_fullsize_fused_ffn_64_row_blocks():
+    """The fused FFN with 64-row blocks at full size: cfg2 with a publish tile of 64 rows (the row block must hold
+    whole publish tiles), every row of staging and out against both oracles, then the unfused path on the same
+    buffers."""
+    name = "cfg2"
+    print("case full-size cfg2, tile_m 64, fused FFN", flush=True)
+    inp = W.make_inputs(dict(W.CONFIGS[name], tile_m=64))
+    cache = {}
+    B, inp, p, buf = _run(name, 1, 0, inp=inp, fuse_ffn=1)
+    _check(B, inp, p, buf, 1, name, cache)
+    B, inp, p, buf = _run(name, 1, 0, inp=inp, buf=buf, epoch=2)
     _check(B, inp, p, buf, 1, name, cache)

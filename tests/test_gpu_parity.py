@@ -21,16 +21,18 @@ def _dev(inp, names):
     return {n: (inp[n].cuda() if inp.get(n) is not None else None) for n in names}
 
 
-def _problem(B, cfg, signal_mode=1, fence_scope=0, epoch=1, group_size=0, scheduler=0, capacity=0, wait_ticks=0):
+def _problem(B, cfg, signal_mode=1, fence_scope=0, epoch=1, group_size=0, scheduler=0, capacity=0, wait_ticks=0,
+             fuse_ffn=0):
     return B.problem(cfg["T"], cfg["d"], cfg["E"], cfg["k"], cfg["f"], cfg["R"], cfg["dtype"], tile_m=cfg["tile_m"],
                      tile_n=cfg["tile_n"], signal_mode=signal_mode, fence_scope=fence_scope, epoch=epoch,
-                     group_size=group_size, scheduler=scheduler, capacity=capacity, wait_ticks=wait_ticks)
+                     group_size=group_size, scheduler=scheduler, capacity=capacity, wait_ticks=wait_ticks,
+                     fuse_ffn=fuse_ffn)
 
 
 def run_forward(B, inp, signal_mode, fence_scope, epoch=1, buf=None, group_size=0, scheduler=0, capacity=0,
-                wait_ticks=0):
+                wait_ticks=0, fuse_ffn=0):
     cfg = inp["cfg"]
-    p = _problem(B, cfg, signal_mode, fence_scope, epoch, group_size, scheduler, capacity, wait_ticks)
+    p = _problem(B, cfg, signal_mode, fence_scope, epoch, group_size, scheduler, capacity, wait_ticks, fuse_ffn)
     buf = buf or B.Buffers(p)
     d = _dev(inp, ("x", "Wg", "gate_bias", "W1", "W3", "W2"))
     if cfg["prerouted"] is not None:
@@ -698,3 +700,42 @@ def test_probe_mfma_runs_and_keeps_its_work():
     assert torch.equal(sink, torch.full_like(sink, 3 * 16.0 * 16 * 16))
     with pytest.raises(B.MoeError):
         B.moe_probe_mfma(frag, 0, 8, sink)
+
+
+@pytest.mark.parametrize("name,tile_m", [("mini_decode", 32), ("mini_bf16", 64), ("mini_skew", 64), ("mini_skew", 32),
+                                         ("mini_odd", 64), ("mini_pre", 32), ("mini_large", 64)])
+@pytest.mark.parametrize("signal_mode", [0, 1])
+def test_megakernel_fused_ffn(name, tile_m, signal_mode):
+    """The fused FFN (a workgroup takes a row block through both GEMMs, h stays in LDS): same results as the
+    oracle to the same bars, both row-block heights, both signaling modes, reused buffers; and bit-identical
+    staging and out to the unfused path (same products, same order of accumulation per element)."""
+    B = _binding()
+    inp = W.make_inputs(dict(W.CONFIGS[name], tile_m=tile_m))
+    print(f"case fused {name} tile_m {tile_m} mode {signal_mode}", flush=True)
+    p, buf = run_forward(B, inp, signal_mode, 0, fuse_ffn=1)
+    ref = check_against_oracle(B, inp, p, buf, signal_mode)
+    st, out = buf.staging.clone(), buf.out.clone()
+    p, buf = run_forward(B, inp, signal_mode, 0, epoch=2, buf=buf, fuse_ffn=1)
+    check_against_oracle(B, inp, p, buf, signal_mode, ref)
+    p, buf = run_forward(B, inp, signal_mode, 0, epoch=3, buf=buf, fuse_ffn=0)
+    check_against_oracle(B, inp, p, buf, signal_mode, ref)
+    assert torch.equal(buf.staging.view(torch.int16), st.view(torch.int16)) and torch.equal(buf.out.view(torch.int16), out.view(torch.int16))
+
+
+def test_fused_ffn_limits():
+    B = _binding()
+    # declined when the problem is planned: publish tile taller than the row block, ready-queue scheduler, fp32
+    for kw in (dict(tile_m=128), dict(tile_m=32, scheduler=1), dict(tile_m=32, dtype="f32")):
+        p = B.problem(128, 1024, 16, 4, 512, 8, kw.get("dtype", "bf16"), tile_m=kw["tile_m"], scheduler=kw.get("scheduler", 0),
+                      fuse_ffn=1)
+        assert B.moe_workspace_bytes(p) == 0, kw
+    # declined at the launch: h of a row block (32 rows x 2048) does not fit the LDS beside the stage buffers
+    p = B.problem(128, 1024, 16, 4, 2048, 8, "bf16", tile_m=32, fuse_ffn=1)
+    buf = B.Buffers(p)
+    x = torch.zeros((128, 1024), dtype=torch.bfloat16, device="cuda")
+    Wg = torch.zeros((1024, 16), dtype=torch.bfloat16, device="cuda")
+    W1 = torch.zeros((16, 1024, 2048), dtype=torch.bfloat16, device="cuda")
+    W2 = torch.zeros((16, 2048, 1024), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.MoeError) as e:
+        B.forward(p, buf, x, Wg, None, W1, W1, W2)
+    assert e.value.status == B.MOE_ERR_UNSUPPORTED
