@@ -174,6 +174,35 @@ def mfma_ceiling(B, torch):
     return out
 
 
+def stream_ceiling(B, torch):
+    """What the CUs of this machine pull in when they do nothing else (the library's probe kernel): bytes/s by source
+    (HBM: every workgroup its own 8 MB of a 2 GB buffer; memory-side cache: all inside 128 MB; L2: all workgroups
+    read the same 2 MB) and by wavefronts per CU.  The megakernel runs 4 wavefronts per CU."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    buf = torch.ones(2 << 30, dtype=torch.uint8, device="cuda")
+    sink = torch.empty(cus * 1024, dtype=torch.int32, device="cuda")
+    per_wg = 8 << 20
+    out = {"compute_units": cus, "bytes_per_workgroup": per_wg, "hbm_peak_gbs": HBM_PEAK_GBS, "rows": []}
+    for source, span, stride in (("hbm", 2 << 30, per_wg), ("memory_side_cache", 128 << 20, 1 << 20), ("l2", 2 << 20, 0)):
+        for waves in (4, 8, 16):
+            for to_lds in (1, 0):
+                fn = lambda: B.moe_probe_stream(buf, span, stride, per_wg, cus, waves, to_lds, sink)
+                for _ in range(2):
+                    fn()
+                torch.cuda.synchronize()
+                evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+                for e0, e1 in evs:
+                    e0.record()
+                    fn()
+                    e1.record()
+                torch.cuda.synchronize()
+                ms = sum(e0.elapsed_time(e1) for e0, e1 in evs) / len(evs)
+                gbs = cus * per_wg / (ms * 1e-3) / 1e9
+                out["rows"].append({"source": source, "wavefronts_per_cu": waves, "into": "lds" if to_lds else "registers",
+                                    "ms": round(ms, 4), "gbs": round(gbs, 1), "gbs_per_cu": round(gbs / cus, 2)})
+    return out
+
+
 def run_workload(name, args, B, torch, W, steps, warmup, with_cpu, with_ops, calibrate=False):
     """Time `steps` launches of the megakernel on workload `name`; -> dict of everything measured."""
     cfg = W.config(name)
@@ -303,6 +332,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known HBM traffic) so that hardware byte "
                          "counters collected around this command can be scaled")
+    ap.add_argument("--stream-ceiling", action="store_true",
+                    help="also measure what this box's CUs stream from HBM, the memory-side cache and L2 with 4, 8 and 16 "
+                         "wavefronts each (the library's probe kernel; 'stream_ceiling')")
     ap.add_argument("--mfma-ceiling", action="store_true",
                     help="also measure what this box's matrix cores deliver with no memory traffic (the library's "
                          "probe kernel) and what the vendor GEMM reaches on one cfg4 expert's shapes ('mfma_ceiling')")
@@ -341,6 +373,8 @@ def main():
                                                    "signaling", "timeline_us", "standalone_ops") if k in sec}
     if args.mfma_ceiling:
         res["mfma_ceiling"] = mfma_ceiling(B, torch)
+    if args.stream_ceiling:
+        res["stream_ceiling"] = stream_ceiling(B, torch)
     if "cpu_baseline" in main_res:
         res["cpu_baseline"] = main_res["cpu_baseline"]
     print(json.dumps(res))

@@ -273,6 +273,22 @@ int moe_combine(const moe_problem_t *p, const void *staging, const uint32_t *fla
  */
 int moe_probe_mfma(const void *frag, int32_t iters, int32_t workgroups, float *sink, void *stream);
 
+/*
+ * Measurement aid, no part of the layer: the rate at which this GPU's CUs pull bytes in when they do nothing else
+ * (what the weight-streaming phases of the layer, which run 4 wavefronts per CU, can be held against on a given
+ * box, by source and by wavefronts per CU).  `workgroups` workgroups of
+ * `wavefronts` (4, 8 or 16) wavefronts, one per CU (each takes 128 KB of LDS), read `bytes_per_workgroup` bytes each
+ * (rounded down to a multiple of wavefronts * 8 KB) from `buf` (device, at least span_bytes): workgroup w starts at
+ * byte (w * stride_bytes) mod span_bytes and wraps inside the first span_bytes, so that a span far beyond the caches
+ * with stride = bytes_per_workgroup streams from HBM, and a small span with stride 0 streams from L2.  to_lds = 1:
+ * loads that write straight into LDS, as the GEMM main loop's do; 0: loads into registers.  `sink` (device,
+ * workgroups * wavefronts * 64 words) receives one word per thread so that the work is kept.  span_bytes >= 16 KB,
+ * span_bytes and stride_bytes multiples of 16, else MOE_ERR_INVALID_ARG.  Asynchronous on `stream`; the caller
+ * times it.  Bytes = workgroups * bytes_per_workgroup (rounded as above).
+ */
+int moe_probe_stream(const void *buf, size_t span_bytes, size_t stride_bytes, size_t bytes_per_workgroup,
+                     int32_t workgroups, int32_t wavefronts, int32_t to_lds, uint32_t *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,8 @@ MOE_SCHED_STATIC, MOE_SCHED_READY_QUEUE = 0, 1
 MOE_NUM_STATS = 20
 
 EXPORTS = ("moe_workspace_bytes", "moe_num_flags", "moe_status_string", "moe_workspace_init", "moe_route",
-           "moe_dispatch", "moe_dispatch_noalloc", "moe_megakernel_forward", "moe_combine", "moe_probe_mfma")
+           "moe_dispatch", "moe_dispatch_noalloc", "moe_megakernel_forward", "moe_combine", "moe_probe_mfma",
+           "moe_probe_stream")
 
 
 class MoeProblem(ctypes.Structure):
@@ -58,8 +59,10 @@ _lib.moe_dispatch_noalloc.argtypes = [_pp] + [_vp] * 9
 _lib.moe_megakernel_forward.argtypes = [_pp] + [_vp] * 19
 _lib.moe_combine.argtypes = [_pp] + [_vp] * 7
 _lib.moe_probe_mfma.argtypes = [_vp, ctypes.c_int32, ctypes.c_int32, _vp, _vp]
+_lib.moe_probe_stream.argtypes = [_vp, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32,
+                                  ctypes.c_int32, _vp, _vp]
 for _n in ("moe_workspace_init", "moe_route", "moe_dispatch", "moe_dispatch_noalloc", "moe_megakernel_forward",
-           "moe_combine", "moe_probe_mfma"):
+           "moe_combine", "moe_probe_mfma", "moe_probe_stream"):
     getattr(_lib, _n).restype = ctypes.c_int
 
 
@@ -140,6 +143,11 @@ def moe_combine(p, staging, flags, slot_flag, topk_w, out, status_dev, stream=No
 
 def moe_probe_mfma(frag, iters, workgroups, sink, stream=None):
     _check(_lib.moe_probe_mfma(_ptr(frag), int(iters), int(workgroups), _ptr(sink), _stream(stream)), "moe_probe_mfma")
+
+
+def moe_probe_stream(buf, span_bytes, stride_bytes, bytes_per_workgroup, workgroups, wavefronts, to_lds, sink, stream=None):
+    _check(_lib.moe_probe_stream(_ptr(buf), int(span_bytes), int(stride_bytes), int(bytes_per_workgroup), int(workgroups),
+                                 int(wavefronts), int(to_lds), _ptr(sink), _stream(stream)), "moe_probe_stream")
 
 
 class Buffers:

@@ -104,6 +104,52 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_mfma(const uint4 *frag, i
     sink[(size_t)blockIdx.x * kThreads + threadIdx.x] = s;
 }
 
+// Measurement aid (moe_probe_stream): nothing but loads.  Every workgroup of NT threads reads `bytes_per_wg` bytes
+// that start at byte (workgroup * stride) % span of `buf` and wrap inside its first `span` bytes, 1 KB per wavefront
+// and instruction (16 bytes per lane, consecutive), kStreamDepth instructions per wavefront issued back to back and
+// half of them awaited before the next batch.  LDS form: global_load_lds_dwordx4 into a per-wavefront ring in LDS,
+// the way the GEMM main loop loads its stages; register form: global_load_dwordx4, the values folded into one word.
+// What this reaches is what a CU can pull in with that many wavefronts, from HBM (span far beyond the caches), from
+// the memory-side cache or from L2 (small span, stride 0), whatever else the kernel that is compared with it does.
+constexpr int kStreamDepth = 8;
+template <int NT, bool TO_LDS>
+__global__ __launch_bounds__(NT, 1) void k_probe_stream(const char *buf, size_t span, size_t stride, size_t bytes_per_wg, u32 *sink) {
+    extern __shared__ __align__(1024) char stream_lds[];
+    constexpr int NW = NT / 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const size_t start = ((size_t)blockIdx.x * stride) % span;
+    const size_t n_instr = bytes_per_wg / ((size_t)NW * 1024);
+    u32x4_t acc = u32x4_t{0u, 0u, 0u, 0u};
+    const size_t mine = (size_t)wave * 1024 + (size_t)lane * 16;
+    if (TO_LDS) {
+        const u32 ring = lds_offset(stream_lds) + (u32)wave * (kStreamDepth * 1024);
+        for (size_t it = 0; it + kStreamDepth <= n_instr; it += kStreamDepth) {
+#pragma unroll
+            for (int u = 0; u < kStreamDepth; ++u) {
+                const char *src = buf + (start + (it + u) * ((size_t)NW * 1024) + mine) % span;
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                             :
+                             : "s"(__builtin_amdgcn_readfirstlane(ring + (u32)u * 1024)), "v"(src)
+                             : "m0", "memory");
+            }
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kStreamDepth / 2) : "memory");
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        acc = *(const u32x4_t *)(stream_lds + (size_t)tid * 16);
+    } else {
+        for (size_t it = 0; it + kStreamDepth <= n_instr; it += kStreamDepth) {
+            u32x4_t r[kStreamDepth];
+#pragma unroll
+            for (int u = 0; u < kStreamDepth; ++u)
+                r[u] = *(const u32x4_t *)(buf + (start + (it + u) * ((size_t)NW * 1024) + mine) % span);
+#pragma unroll
+            for (int u = 0; u < kStreamDepth; ++u) acc ^= r[u];
+        }
+    }
+    sink[(size_t)blockIdx.x * NT + tid] = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+}
+
 // standalone dispatch as one launch (see dispatch_fused_task); and the row movement of the histogram form by
 // token (ragged layout), which moves nothing unless the histogram accounts for every slot
 template <int STORE>
@@ -878,6 +924,30 @@ int moe_megakernel_forward(const moe_problem_t *p, const void *x, const void *Wg
         case TK_FM: return launch_mega<FusedPolicy<CfgFM>, FusedPolicy<CfgFM>>(pl, a, st);
         default: return launch_mega<Bf16Policy<CfgS>, Bf16Policy<CfgS>>(pl, a, st);
     }
+}
+
+int moe_probe_stream(const void *buf, size_t span_bytes, size_t stride_bytes, size_t bytes_per_workgroup, int32_t workgroups,
+                     int32_t wavefronts, int32_t to_lds, uint32_t *sink, void *stream) {
+    if (!buf || !sink || workgroups < 1 || workgroups > 65536) return MOE_ERR_INVALID_ARG;
+    if (wavefronts != 4 && wavefronts != 8 && wavefronts != 16) return MOE_ERR_INVALID_ARG;
+    if (to_lds != 0 && to_lds != 1) return MOE_ERR_INVALID_ARG;
+    // every piece is 16 bytes at a multiple of 16 below span_bytes
+    if (span_bytes < 16 * 1024 || span_bytes % 16 != 0 || stride_bytes % 16 != 0 || bytes_per_workgroup < 1) return MOE_ERR_INVALID_ARG;
+    // the whole LDS of a CU minus a margin: one workgroup per CU, whatever its size
+    const size_t smem = 128 * 1024;
+    hipStream_t st = (hipStream_t)stream;
+    const char *b = (const char *)buf;
+    int rc;
+#define MOE_STREAM_CASE(NT, L)                                                                                          \
+    if (wavefronts * 64 == NT && to_lds == L) {                                                                         \
+        if ((rc = set_smem(k_probe_stream<NT, L != 0>, smem))) return rc;                                               \
+        hipLaunchKernelGGL((k_probe_stream<NT, L != 0>), dim3(workgroups), dim3(NT), smem, st, b, span_bytes, stride_bytes, \
+                           bytes_per_workgroup, sink);                                                                  \
+    }
+    MOE_STREAM_CASE(256, 0) MOE_STREAM_CASE(256, 1) MOE_STREAM_CASE(512, 0) MOE_STREAM_CASE(512, 1)
+    MOE_STREAM_CASE(1024, 0) MOE_STREAM_CASE(1024, 1)
+#undef MOE_STREAM_CASE
+    return hip_ok(hipGetLastError());
 }
 
 int moe_probe_mfma(const void *frag, int32_t iters, int32_t workgroups, float *sink, void *stream) {

@@ -702,6 +702,48 @@ def test_probe_mfma_runs_and_keeps_its_work():
         B.moe_probe_mfma(frag, 0, 8, sink)
 
 
+@pytest.mark.parametrize("waves", [4, 8, 16])
+@pytest.mark.parametrize("to_lds", [0, 1])
+def test_probe_stream_reads_what_it_says(waves, to_lds):
+    """The streaming measurement aid reads exactly the pieces its contract names: the word a thread leaves in `sink`
+    is rebuilt on the CPU from the buffer (register form: XOR of every word the lane loaded; LDS form: XOR of the
+    four words that ended up at byte 16 * thread of the workgroup's LDS, i.e. of a piece of the last batch)."""
+    B = _binding()
+    span, stride, wgs, depth = 1 << 20, 4096 + 48, 5, 8
+    per_wg = waves * 1024 * (3 * depth + 5)  # rounds down to three batches of eight loads per wavefront
+    rng = np.random.default_rng(17)
+    host = rng.integers(0, 1 << 32, size=span // 4, dtype=np.uint32)
+    buf = torch.from_numpy(host.view(np.int32)).cuda()
+    nt = waves * 64
+    sink = torch.full((wgs * nt,), -1, dtype=torch.int32, device="cuda")
+    B.moe_probe_stream(buf, span, stride, per_wg, wgs, waves, to_lds, sink)
+    torch.cuda.synchronize()
+    got = sink.cpu().numpy().view(np.uint32).reshape(wgs, nt)
+    n_instr = 3 * depth
+
+    def piece(off):  # XOR of the four words at byte offset off
+        w = host[off // 4: off // 4 + 4]
+        return int(w[0] ^ w[1] ^ w[2] ^ w[3])
+
+    for w in range(wgs):
+        start = (w * stride) % span
+        for tid in range(nt):
+            if to_lds:
+                at = tid * 16  # byte of the workgroup's LDS: ring of wavefront at // 8192, load at % 8192 // 1024 of a batch
+                wave, u, lane = at // (depth * 1024), (at % (depth * 1024)) // 1024, (at % 1024) // 16
+                want = piece((start + (n_instr - depth + u) * waves * 1024 + wave * 1024 + lane * 16) % span)
+            else:
+                wave, lane = tid // 64, tid % 64
+                want = 0
+                for i in range(n_instr):
+                    want ^= piece((start + i * waves * 1024 + wave * 1024 + lane * 16) % span)
+            assert int(got[w, tid]) == want, (w, tid)
+    for bad in (dict(waves=3), dict(span=span + 8), dict(stride=8), dict(span=1024)):
+        with pytest.raises(B.MoeError):
+            B.moe_probe_stream(buf, bad.get("span", span), bad.get("stride", stride), per_wg, wgs, bad.get("waves", waves),
+                               to_lds, sink)
+
+
 @pytest.mark.parametrize("name,tile_m", [("mini_decode", 32), ("mini_bf16", 64), ("mini_skew", 64), ("mini_skew", 32),
                                          ("mini_odd", 64), ("mini_pre", 32), ("mini_large", 64)])
 @pytest.mark.parametrize("signal_mode", [0, 1])
