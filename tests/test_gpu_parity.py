@@ -702,6 +702,47 @@ def test_probe_mfma_runs_and_keeps_its_work():
         B.moe_probe_mfma(frag, 0, 8, sink)
 
 
+def test_megakernel_replayed_from_a_captured_graph():
+    """A serving loop launches the layer from a captured HIP graph: the library only launches kernels on the stream it
+    is given (no allocation, no memset, no synchronisation; kernel attributes are set by the first eager call), and the
+    megakernel leaves its workspace ready for the next launch.  The graph holds what one step needs: flags cleared
+    by a fill kernel (the epoch is baked into the captured launch), outputs poisoned, one forward.  Every replay,
+    with eager launches and synchronisations of the program's own in between, must reproduce the eager result bit
+    for bit."""
+    B = _binding()
+    inp = W.make_inputs("mini_bf16")
+    cfg = inp["cfg"]
+    d = _dev(inp, ("x", "Wg", "gate_bias", "W1", "W3", "W2"))
+    p, buf = run_forward(B, inp, 1, 0, epoch=5)  # eager: reference result, and the one-time host-side set-up
+    check_against_oracle(B, inp, p, buf, 1)
+    want = {n: getattr(buf, n).clone() for n in ("out", "staging", "topk_idx", "perm", "counts")}
+    other = B.Buffers(p)  # the program's own eager work between replays uses other buffers
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        buf.flags.zero_()
+        buf.staging.fill_(float("nan"))
+        buf.out.fill_(float("nan"))
+        B.forward(p, buf, d["x"], d["Wg"], d["gate_bias"], d["W1"], d["W3"], d["W2"])
+    torch.cuda.synchronize()
+    for rep in range(4):
+        print(f"case graph replay {rep}", flush=True)
+        buf.out.fill_(0.25)  # whatever the last replay left must not be what this one is checked on
+        buf.perm.fill_(-7)
+        graph.replay()
+        torch.cuda.synchronize()
+        for n, ref in want.items():
+            got = getattr(buf, n)
+            assert torch.equal(got.view(torch.uint8), ref.view(torch.uint8)), (rep, n)
+        assert int(buf.stats[7].item()) == 0
+        p2 = _problem(B, cfg, 1, 0, epoch=100 + rep)
+        other.flags.zero_()
+        B.forward(p2, other, d["x"], d["Wg"], d["gate_bias"], d["W1"], d["W3"], d["W2"])
+        torch.cuda.synchronize()
+        assert torch.equal(other.out.view(torch.uint8), want["out"].view(torch.uint8))
+
+
 @pytest.mark.parametrize("waves", [4, 8, 16])
 @pytest.mark.parametrize("to_lds", [0, 1])
 def test_probe_stream_reads_what_it_says(waves, to_lds):
