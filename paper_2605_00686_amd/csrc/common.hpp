@@ -163,9 +163,14 @@ __device__ __forceinline__ void fence_acquire(int system_scope) {
 // (measured: 1.5 % of the whole layer on the two large workloads).  The instruction is written out
 // because no builtin sets these cache-policy bits on a 16-byte store; every caller follows its
 // stores with sync_stores(), which waits for them.
+// The s_nop belongs to the store: a vector store of more than 8 bytes reads its data registers for a few cycles
+// after it issues, and a vector ALU instruction that overwrites one of them in the very next slots changes what
+// the later lanes store.  For its own stores the compiler keeps that distance; it cannot see into this statement
+// and may reuse the registers at once (seen in a variant that stored accumulators back to back: the upper lanes
+// of a 16-byte piece stored the next piece's address bits).
 __device__ __forceinline__ void store_tile16(char *p, const uint4 &v) {
     const u32x4_t w = {v.x, v.y, v.z, v.w};
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(w));
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(p), "v"(w));
 }
 
 // Workgroup barrier that also waits for this wavefront's outstanding global

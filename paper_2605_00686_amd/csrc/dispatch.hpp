@@ -429,7 +429,7 @@ template <int STORE>
 __device__ __forceinline__ void store_row16(char *p, const uint4 &v) {
     const u32x4_t w = {v.x, v.y, v.z, v.w};
     if (STORE == 0)
-        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(w) : "memory");
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" ::"v"(p), "v"(w) : "memory");  // (s_nop: see store_tile16)
     else
         __builtin_nontemporal_store(w, (u32x4_t *)p);
 }
