@@ -93,3 +93,38 @@ def test_null_pointers_and_zero_epoch(B):
     assert lib.moe_workspace_init(ctypes.byref(p), None, None) == B.MOE_ERR_WORKSPACE
     fake = ctypes.c_void_p(0x1008)  # misaligned workspace is refused before any launch
     assert lib.moe_workspace_init(ctypes.byref(p), fake, None) == B.MOE_ERR_WORKSPACE
+
+
+def test_header_is_plain_c_and_links_from_c(B, tmp_path):
+    """The boundary is a C ABI: include/moe.h compiles as strict C99 (no C++ in it), a C program links against the
+    library without anything else on its link line, and what it gets from the host-only calls is what the Python
+    binding gets."""
+    import subprocess
+    src = tmp_path / "abi.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "moe.h"
+int main(void) {
+    moe_problem_t p;
+    memset(&p, 0, sizeof p);
+    p.T = 4096; p.d = 2048; p.E = 128; p.k = 8; p.f = 768; p.R = 8;
+    p.dtype = MOE_DT_BF16; p.signal_mode = MOE_SIGNAL_PER_DEST; p.fence_scope = MOE_SCOPE_AGENT; p.epoch = 1;
+    printf("%zu %zu %s|%s\n", moe_workspace_bytes(&p), moe_num_flags(&p), moe_status_string(MOE_OK),
+           moe_status_string(MOE_ERR_UNSUPPORTED));
+    p.k = 200;  /* more experts per token than experts: no workspace size */
+    printf("%zu\n", moe_workspace_bytes(&p));
+    /* a compute entry point refuses a missing problem before it touches a device */
+    printf("%d\n", moe_combine(NULL, NULL, NULL, NULL, NULL, NULL, NULL, NULL));
+    return 0;
+}
+''')
+    exe = tmp_path / "abi"
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", inc, str(src), "-o", str(exe), LIB,
+                    "-Wl,-rpath," + os.path.dirname(LIB)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    p = B.problem(4096, 2048, 128, 8, 768, 8, "bf16")
+    assert out[0] == f"{B.moe_workspace_bytes(p)} {B.moe_num_flags(p)} ok|unsupported problem"
+    assert out[1] == "0"
+    assert int(out[2]) == B.MOE_ERR_INVALID_ARG
