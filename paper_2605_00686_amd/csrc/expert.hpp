@@ -42,6 +42,7 @@ struct F32Policy {
 template <class C>
 struct FusedPolicy : Bf16Policy<C> {
     static constexpr bool FUSED = true;
+    static constexpr int MIN_WAVES = 1;  // the row block's h takes the LDS a second workgroup would need
 };
 // LDS after the GEMM region: per-row slot / destination, publish row-tile list
 template <class P>
